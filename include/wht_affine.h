@@ -1,0 +1,113 @@
+/*
+ * wht_affine.h -- C ABI of the Walsh-Hadamard output layer for AMD MI355X (gfx950).
+ *
+ * The layer replaces the dense attention output projection W_O (paper Sec. 4.1, Eq. 1):
+ * for every token n, with x[n,:] the concatenated head outputs (d = heads * d_head, a power of two),
+ *
+ *     z[n,:] = H x[n,:]                    H = H_raw / sqrt(d),  H_raw[j][k] = (-1)^popcount(j & k)
+ *     y[n,:] = alpha (.) z[n,:] + beta     (Eq. 1; alpha, beta in R^d are the only parameters)
+ *
+ * H is the normalised Walsh-Hadamard matrix in Sylvester (natural) order -- the sign block drawn in
+ * Fig. 1 -- so H^T H = I (Sec. 4.1) and H is symmetric.  It is never stored: the kernels run the
+ * log2(d) add/subtract butterfly stages of Fig. 2.
+ *
+ * Backward (the paper gives only the O(d log d) cost, Table 1; the formulas are Eq. 1's chain rule):
+ *
+ *     dx[n,:]   = H (alpha (.) dy[n,:])
+ *     dalpha[j] = sum_n dy[n,j] * z[n,j]        z is recomputed from x, never stored
+ *     dbeta[j]  = sum_n dy[n,j]
+ *
+ * Conventions for every entry point
+ *   - Every pointer is a DEVICE pointer owned by the caller (the `stream` handle aside).  The
+ *     library never allocates, frees or synchronises; work is enqueued on `stream` (a hipStream_t
+ *     passed as void*, NULL = the default stream) and the call returns at once.
+ *   - x, y, dy, dx are row-major [N, d], contiguous (leading dimension d), of type `dtype`.
+ *     alpha, beta, dalpha, dbeta are float32 [d] whatever `dtype` is.
+ *   - bfloat16 tensors are computed in float32 internally and rounded to nearest-even on store.
+ *   - All tensor pointers must be 16-byte aligned.  y may alias x exactly, dx may alias dy or x
+ *     exactly; partial overlap is undefined.
+ *   - The return value is a wht_status_t.  Arguments are validated before anything is enqueued, so
+ *     a failed call has no side effects.  N = 0 is valid (backward then zero-fills dalpha, dbeta).
+ *   - d must be a power of two with WHT_MIN_D <= d <= WHT_MAX_D; anything else (including the
+ *     paper's own d = 768 and 1536, for which it does not say how H is built) is WHT_ERR_BAD_DIM.
+ */
+#ifndef WHT_AFFINE_H
+#define WHT_AFFINE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define WHT_MIN_D 32
+#define WHT_MAX_D 16384
+
+typedef enum {
+    WHT_DTYPE_F32  = 0,   /* x, y, dy, dx are IEEE binary32 */
+    WHT_DTYPE_BF16 = 1    /* x, y, dy, dx are bfloat16 (upper half of binary32) */
+} wht_dtype_t;
+
+typedef enum {
+    WHT_OK             = 0,
+    WHT_ERR_NULL_PTR   = 1,   /* a required pointer is NULL */
+    WHT_ERR_BAD_DIM    = 2,   /* d not a power of two in [WHT_MIN_D, WHT_MAX_D], or N < 0 */
+    WHT_ERR_BAD_DTYPE  = 3,
+    WHT_ERR_MISALIGNED = 4,   /* a tensor pointer is not 16-byte aligned */
+    WHT_ERR_WORKSPACE  = 5,   /* workspace NULL or smaller than wht_affine_backward_workspace_bytes */
+    WHT_ERR_LAUNCH     = 6    /* the HIP runtime refused a launch (hipGetLastError() != hipSuccess) */
+} wht_status_t;
+
+/*
+ * Forward, Eq. 1:  y = alpha (.) (H x) + beta.
+ *   x      in   [N,d] dtype     read once
+ *   alpha  in   [d]   float32
+ *   beta   in   [d]   float32
+ *   y      out  [N,d] dtype     written once
+ */
+int wht_affine_forward(const void *x, const float *alpha, const float *beta, void *y,
+                       int64_t N, int32_t d, int32_t dtype, void *stream);
+
+/*
+ * Bytes of device scratch wht_affine_backward needs for (N, d, dtype): per-workgroup partial sums
+ * of dalpha and dbeta, float32.  Depends on d only through the launch shape; 0 when N = 0 or when
+ * the arguments are invalid.  Needs no GPU.
+ */
+size_t wht_affine_backward_workspace_bytes(int64_t N, int32_t d, int32_t dtype);
+
+/*
+ * Backward of Eq. 1 (see the header comment).
+ *   dy      in   [N,d] dtype
+ *   x       in   [N,d] dtype      the forward input; z = H x is recomputed
+ *   alpha   in   [d]   float32
+ *   dx      out  [N,d] dtype      written once
+ *   dalpha  out  [d]   float32    overwritten (not accumulated into)
+ *   dbeta   out  [d]   float32    overwritten
+ *   workspace    device scratch, 16-byte aligned, at least ..._workspace_bytes(N, d, dtype) bytes;
+ *                contents on entry are ignored, contents on return are unspecified
+ * The reduction over tokens has a fixed order: results are bit-reproducible run to run.
+ */
+int wht_affine_backward(const void *dy, const void *x, const float *alpha,
+                        void *dx, float *dalpha, float *dbeta,
+                        int64_t N, int32_t d, int32_t dtype,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Measurement aid, not part of the layer: dst[i] = src[i] for `bytes` bytes (a multiple of 16) with
+ * the same 16-byte-per-lane access pattern the layer's kernels use.  It gives the benchmark the
+ * bandwidth a plain streaming kernel reaches on this GPU and a known-size reference for the
+ * profiler's HBM byte counters.  src, dst: device, 16-byte aligned, non-overlapping.
+ */
+int wht_affine_copy_baseline(const void *src, void *dst, size_t bytes, void *stream);
+
+/* Static, NUL-terminated description of a wht_status_t (host memory, never freed). */
+const char *wht_affine_status_string(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int wht_affine_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WHT_AFFINE_H */

@@ -1,0 +1,19 @@
+"""MI355X-native Walsh-Hadamard output layer: y = alpha (.) (H x) + beta (paper Sec. 4.1, Eq. 1).
+
+All arithmetic runs in the HIP kernels of libwht_affine.so (C ABI in include/wht_affine.h); this
+package only marshals arguments.  There is no CPU fallback: without the built library, or without a
+GPU, the calls raise.
+"""
+from .binding import (  # noqa: F401
+    DTYPE_BF16,
+    DTYPE_F32,
+    WhtAffineError,
+    library,
+    library_path,
+    wht_affine_backward,
+    wht_affine_backward_workspace_bytes,
+    wht_affine_copy_baseline,
+    wht_affine_forward,
+    wht_affine_status_string,
+    wht_affine_version,
+)

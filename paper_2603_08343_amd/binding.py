@@ -1,0 +1,189 @@
+"""ctypes binding of libwht_affine.so -- same names as the C ABI (include/wht_affine.h).
+
+Argument marshalling only: torch supplies device memory and the stream, every step of the layer
+runs in the HIP kernels.  The `*_raw` calls take integer device addresses and return the status
+code; the tensor calls check shapes/dtypes, allocate outputs and the backward workspace with torch,
+and raise WhtAffineError on a non-zero status.
+"""
+import ctypes
+import os
+
+DTYPE_F32 = 0
+DTYPE_BF16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libwht_affine.so")
+_lib = None
+
+EXPORTS = (
+    "wht_affine_forward",
+    "wht_affine_backward_workspace_bytes",
+    "wht_affine_backward",
+    "wht_affine_copy_baseline",
+    "wht_affine_status_string",
+    "wht_affine_version",
+)
+
+
+class WhtAffineError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({wht_affine_status_string(status)})")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def library():
+    """The loaded shared library.  Raises if it has not been built: there is no fallback path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2603_08343_amd.build` "
+                "(hipcc, gfx950). The layer has no CPU or eager fallback.")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+        lib.wht_affine_forward.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp]
+        lib.wht_affine_forward.restype = ctypes.c_int
+        lib.wht_affine_backward_workspace_bytes.argtypes = [i64, i32, i32]
+        lib.wht_affine_backward_workspace_bytes.restype = sz
+        lib.wht_affine_backward.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, vp, sz, vp]
+        lib.wht_affine_backward.restype = ctypes.c_int
+        lib.wht_affine_copy_baseline.argtypes = [vp, vp, sz, vp]
+        lib.wht_affine_copy_baseline.restype = ctypes.c_int
+        lib.wht_affine_status_string.argtypes = [ctypes.c_int]
+        lib.wht_affine_status_string.restype = ctypes.c_char_p
+        lib.wht_affine_version.argtypes = []
+        lib.wht_affine_version.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+# ------------------------------------------------------------------ raw calls (addresses, status)
+
+def wht_affine_forward_raw(x, alpha, beta, y, N, d, dtype, stream=0) -> int:
+    return library().wht_affine_forward(x, alpha, beta, y, N, d, dtype, stream)
+
+
+def wht_affine_backward_raw(dy, x, alpha, dx, dalpha, dbeta, N, d, dtype, workspace, workspace_bytes,
+                            stream=0) -> int:
+    return library().wht_affine_backward(dy, x, alpha, dx, dalpha, dbeta, N, d, dtype, workspace,
+                                         workspace_bytes, stream)
+
+
+def wht_affine_backward_workspace_bytes(N, d, dtype) -> int:
+    return int(library().wht_affine_backward_workspace_bytes(N, d, dtype))
+
+
+def wht_affine_status_string(status: int) -> str:
+    return library().wht_affine_status_string(int(status)).decode()
+
+
+def wht_affine_version() -> int:
+    return int(library().wht_affine_version())
+
+
+# ------------------------------------------------------------------ tensor calls
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        raise RuntimeError("wht_affine needs an AMD GPU (gfx950); there is no CPU fallback")
+    return torch
+
+
+def _dtype_code(t, torch):
+    if t.dtype == torch.float32:
+        return DTYPE_F32
+    if t.dtype == torch.bfloat16:
+        return DTYPE_BF16
+    raise TypeError(f"x must be float32 or bfloat16, got {t.dtype}")
+
+
+def _check_io(t, name, torch, like=None):
+    if not t.is_cuda or not t.is_contiguous() or t.dim() != 2:
+        raise ValueError(f"{name} must be a contiguous [N,d] GPU tensor")
+    if like is not None and (t.shape != like.shape or t.dtype != like.dtype or t.device != like.device):
+        raise ValueError(f"{name} must match x in shape, dtype and device")
+
+
+def _check_param(p, name, d, x, torch):
+    if not p.is_cuda or p.dtype != torch.float32 or p.shape != (d,) or not p.is_contiguous() \
+            or p.device != x.device:
+        raise ValueError(f"{name} must be a contiguous float32 [d] tensor on x's device")
+
+
+def _stream_handle(stream, torch, device):
+    s = stream if stream is not None else torch.cuda.current_stream(device)
+    return s.cuda_stream
+
+
+def wht_affine_forward(x, alpha, beta, y=None, stream=None):
+    """y = alpha (.) (H x) + beta  (Eq. 1).  x: [N,d] float32|bfloat16 on the GPU; alpha, beta: [d] float32."""
+    torch = _torch()
+    _check_io(x, "x", torch)
+    N, d = x.shape
+    _check_param(alpha, "alpha", d, x, torch)
+    _check_param(beta, "beta", d, x, torch)
+    if y is None:
+        y = torch.empty_like(x)
+    else:
+        _check_io(y, "y", torch, like=x)
+    with torch.cuda.device(x.device):
+        rc = wht_affine_forward_raw(x.data_ptr(), alpha.data_ptr(), beta.data_ptr(), y.data_ptr(), N, d,
+                                    _dtype_code(x, torch), _stream_handle(stream, torch, x.device))
+    if rc != 0:
+        raise WhtAffineError(rc, "wht_affine_forward")
+    return y
+
+
+def wht_affine_backward(dy, x, alpha, dx=None, dalpha=None, dbeta=None, workspace=None, stream=None):
+    """Returns (dx, dalpha, dbeta) with dx = H(alpha (.) dy), dalpha = sum_n dy (.) Hx, dbeta = sum_n dy."""
+    torch = _torch()
+    _check_io(x, "x", torch)
+    _check_io(dy, "dy", torch, like=x)
+    N, d = x.shape
+    _check_param(alpha, "alpha", d, x, torch)
+    code = _dtype_code(x, torch)
+    if dx is None:
+        dx = torch.empty_like(x)
+    else:
+        _check_io(dx, "dx", torch, like=x)
+    if dalpha is None:
+        dalpha = torch.empty(d, dtype=torch.float32, device=x.device)
+    else:
+        _check_param(dalpha, "dalpha", d, x, torch)
+    if dbeta is None:
+        dbeta = torch.empty(d, dtype=torch.float32, device=x.device)
+    else:
+        _check_param(dbeta, "dbeta", d, x, torch)
+    need = wht_affine_backward_workspace_bytes(N, d, code)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    elif not workspace.is_cuda or not workspace.is_contiguous() or workspace.device != x.device:
+        raise ValueError("workspace must be a contiguous GPU tensor on x's device")
+    ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(x.device):
+        rc = wht_affine_backward_raw(dy.data_ptr(), x.data_ptr(), alpha.data_ptr(), dx.data_ptr(),
+                                     dalpha.data_ptr(), dbeta.data_ptr(), N, d, code,
+                                     workspace.data_ptr(), ws_bytes,
+                                     _stream_handle(stream, torch, x.device))
+    if rc != 0:
+        raise WhtAffineError(rc, "wht_affine_backward")
+    return dx, dalpha, dbeta
+
+
+def wht_affine_copy_baseline(src, dst, stream=None):
+    """dst <- src with the kernels' access pattern (measurement aid)."""
+    torch = _torch()
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst must have the same size in bytes")
+    with torch.cuda.device(src.device):
+        rc = library().wht_affine_copy_baseline(src.data_ptr(), dst.data_ptr(), nbytes,
+                                                _stream_handle(stream, torch, src.device))
+    if rc != 0:
+        raise WhtAffineError(rc, "wht_affine_copy_baseline")
+    return dst

@@ -1,0 +1,579 @@
+// HIP kernels (gfx950) and C ABI of the Walsh-Hadamard output layer
+//     y = alpha (.) (H x) + beta                                   (paper Sec. 4.1, Eq. 1)
+// and its backward.  H = H_raw / sqrt(d) in Sylvester order (Fig. 1); H_raw x is computed by the
+// add/subtract butterfly stages of Fig. 2, scheduled by wht_plan.h; 1/sqrt(d) is folded into alpha.
+// Every tensor is read from / written to HBM exactly once, 16 bytes per lane, with the affine fused
+// into the transform's epilogue.  No matrix is stored and no MFMA is used: the work is adds.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <type_traits>
+
+#include "../../include/wht_affine.h"
+#include "wht_plan.h"
+
+namespace wht {
+
+// ------------------------------------------------------------------------------------------------
+// small helpers
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// I/O element traits: how one 16-byte global vector maps to float32 registers.
+struct IoF32 {
+    using elem_t = float;
+    static constexpr int kLogVec = 2;   // 4 elements per 16 bytes
+    static __device__ __forceinline__ void unpack(const uint4& raw, float* out) {
+        out[0] = __uint_as_float(raw.x); out[1] = __uint_as_float(raw.y);
+        out[2] = __uint_as_float(raw.z); out[3] = __uint_as_float(raw.w);
+    }
+    static __device__ __forceinline__ uint4 pack(const float* in) {
+        return make_uint4(__float_as_uint(in[0]), __float_as_uint(in[1]),
+                          __float_as_uint(in[2]), __float_as_uint(in[3]));
+    }
+};
+
+struct IoBF16 {
+    using elem_t = uint16_t;
+    static constexpr int kLogVec = 3;   // 8 elements per 16 bytes
+    // bfloat16 is the upper half of binary32: widening is a shift / a mask
+    static __device__ __forceinline__ void unpack(const uint4& raw, float* out) {
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i]     = __uint_as_float(w[i] << 16);
+            out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    // round to nearest even (the hardware's packed float32 -> bfloat16 convert)
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+        f32x2 f = {lo, hi};
+        bf16x2 b = __builtin_convertvector(f, bf16x2);
+        return __builtin_bit_cast(uint32_t, b);
+    }
+    static __device__ __forceinline__ uint4 pack(const float* in) {
+        return make_uint4(pack2(in[0], in[1]), pack2(in[2], in[3]),
+                          pack2(in[4], in[5]), pack2(in[6], in[7]));
+    }
+};
+
+// ------------------------------------------------------------------------------------------------
+// per-(d, dtype) configuration
+
+template <int LOGD, int LOGE, class Io>
+struct Cfg {
+    using io = Io;
+    static constexpr int n = LOGD, e = LOGE, v = Io::kLogVec;
+    static_assert(v <= e && e <= n && e <= kMaxRegBits, "bad tile");
+    static constexpr PlanDesc plan = make_plan(n, e, v);
+    static_assert(plan_is_complete(plan), "every butterfly stage must run exactly once");
+    static constexpr int P = plan.nphase;
+    static constexpr int D = 1 << n;
+    static constexpr int E = 1 << e;            // values per thread
+    static constexpr int V = 1 << v;            // elements per 16-byte vector
+    static constexpr int NV = E / V;            // 16-byte vectors per thread
+    static constexpr int TPT = 1 << (n - e);    // threads per token
+    static constexpr int BT = TPT > 256 ? TPT : 256;   // threads per workgroup
+    static constexpr int G = BT / TPT;          // tokens per workgroup pass
+    static constexpr unsigned kTokenWords = (lds_phys(D - 1) + 1 + 3) & ~3u;
+    static constexpr unsigned kLdsBytes = (P > 1) ? G * kTokenWords * 4u : 16u;
+    static_assert(kLdsBytes <= 160u * 1024u, "token group does not fit LDS");
+};
+
+// Element offset of thread t (within its token) in phase PH.
+template <class C, int PH>
+__device__ __forceinline__ unsigned thread_elem_offset(unsigned t) {
+    unsigned off = 0;
+    static_for<0, C::n - C::e>([&](auto k) {
+        constexpr int K = decltype(k)::value;
+        off |= ((t >> K) & 1u) << C::plan.ph[PH].tb[K];
+    });
+    return off;
+}
+
+// Butterfly stages of phase PH, all in registers: (a, b) -> (a + b, a - b) on register pairs.
+template <class C, int PH>
+__device__ __forceinline__ void run_stages(float (&r)[C::E]) {
+    static_for<0, C::e>([&](auto q) {
+        constexpr int Q = decltype(q)::value;
+        constexpr int bit = C::plan.ph[PH].rb[Q];
+        if constexpr ((C::plan.ph[PH].stages >> bit) & 1u) {
+            static_for<0, C::E>([&](auto i) {
+                constexpr int I = decltype(i)::value;
+                if constexpr (!((I >> Q) & 1)) {
+                    const float a = r[I], b = r[I | (1 << Q)];
+                    r[I] = a + b;
+                    r[I | (1 << Q)] = a - b;
+                }
+            });
+        }
+    });
+}
+
+template <class C, int PH>
+constexpr bool phase_is_vec4() { return C::plan.ph[PH].rb[0] == 0 && C::plan.ph[PH].rb[1] == 1; }
+
+// Registers <-> LDS in the layout of phase PH.  `tok` points at this token's LDS region plus the
+// thread's own (runtime) offset; register offsets are compile-time immediates.
+template <class C, int PH>
+__device__ __forceinline__ void lds_put(const float (&r)[C::E], float* tok) {
+    if constexpr (phase_is_vec4<C, PH>()) {
+        static_for<0, C::E / 4>([&](auto i) {
+            constexpr int I = decltype(i)::value * 4;
+            constexpr unsigned off = lds_phys(reg_elem_offset(C::plan.ph[PH], C::e, I));
+            *reinterpret_cast<float4*>(tok + off) = make_float4(r[I], r[I + 1], r[I + 2], r[I + 3]);
+        });
+    } else {
+        static_for<0, C::E>([&](auto i) {
+            constexpr int I = decltype(i)::value;
+            constexpr unsigned off = lds_phys(reg_elem_offset(C::plan.ph[PH], C::e, I));
+            tok[off] = r[I];
+        });
+    }
+}
+
+template <class C, int PH>
+__device__ __forceinline__ void lds_get(float (&r)[C::E], const float* tok) {
+    if constexpr (phase_is_vec4<C, PH>()) {
+        static_for<0, C::E / 4>([&](auto i) {
+            constexpr int I = decltype(i)::value * 4;
+            constexpr unsigned off = lds_phys(reg_elem_offset(C::plan.ph[PH], C::e, I));
+            const float4 q = *reinterpret_cast<const float4*>(tok + off);
+            r[I] = q.x; r[I + 1] = q.y; r[I + 2] = q.z; r[I + 3] = q.w;
+        });
+    } else {
+        static_for<0, C::E>([&](auto i) {
+            constexpr int I = decltype(i)::value;
+            constexpr unsigned off = lds_phys(reg_elem_offset(C::plan.ph[PH], C::e, I));
+            r[I] = tok[off];
+        });
+    }
+}
+
+// Per-thread constants: LDS word offset of the thread in every phase, element offset in the first
+// and last phase (the global-memory layouts).
+template <class C>
+struct ThreadMap {
+    unsigned lds_off[kMaxPhases];
+    unsigned first_elem, last_elem;
+    __device__ __forceinline__ void init(unsigned t, unsigned slot) {
+        static_for<0, C::P>([&](auto p) {
+            constexpr int PH = decltype(p)::value;
+            lds_off[PH] = slot * C::kTokenWords + lds_phys(thread_elem_offset<C, PH>(t));
+        });
+        first_elem = thread_elem_offset<C, 0>(t);
+        last_elem = thread_elem_offset<C, C::P - 1>(t);
+    }
+};
+
+// H_raw applied to the 2^n values spread over the token's threads.
+//   FORWARD_ORDER: registers enter in the first phase's layout and leave in the last phase's;
+//   otherwise the phases run in reverse (enter in the last layout, leave in the first) -- the
+//   backward pass uses this so that dy can be consumed in the layout z was produced in.
+// Ends with a workgroup barrier when LDS was used, so the caller may reuse LDS at once.
+template <class C, bool FORWARD_ORDER>
+__device__ __forceinline__ void transform(float (&r)[C::E], float* lds, const ThreadMap<C>& tm) {
+    static_for<0, C::P>([&](auto s) {
+        constexpr int S = decltype(s)::value;
+        constexpr int PH = FORWARD_ORDER ? S : C::P - 1 - S;
+        if constexpr (S > 0) lds_get<C, PH>(r, lds + tm.lds_off[PH]);
+        run_stages<C, PH>(r);
+        if constexpr (S + 1 < C::P) {
+            // a middle phase rewrites exactly the words it read, so only the hand-over to the
+            // next layout needs the barrier
+            lds_put<C, PH>(r, lds + tm.lds_off[PH]);
+            __syncthreads();
+        }
+    });
+    if constexpr (C::P > 1) __syncthreads();
+}
+
+// Global <-> registers in the layout of phase PH (first or last): 16 bytes per lane per access.
+template <class C, int PH>
+__device__ __forceinline__ void global_get(float (&r)[C::E], const typename C::io::elem_t* row,
+                                           unsigned thread_elem, bool active) {
+    static_for<0, C::NV>([&](auto c) {
+        constexpr int Cc = decltype(c)::value;
+        constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V);
+        uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+        if (active) raw = *reinterpret_cast<const uint4*>(row + thread_elem + off);
+        C::io::unpack(raw, &r[Cc * C::V]);
+    });
+}
+
+template <class C, int PH>
+__device__ __forceinline__ void global_put(const float (&r)[C::E], typename C::io::elem_t* row,
+                                           unsigned thread_elem, bool active) {
+    static_for<0, C::NV>([&](auto c) {
+        constexpr int Cc = decltype(c)::value;
+        constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V);
+        if (active) *reinterpret_cast<uint4*>(row + thread_elem + off) = C::io::pack(&r[Cc * C::V]);
+    });
+}
+
+// float32 parameter vector -> registers in the layout of phase PH, times `scale`.
+template <class C, int PH>
+__device__ __forceinline__ void param_get(float (&r)[C::E], const float* p, unsigned thread_elem,
+                                          float scale) {
+    static_for<0, C::E / 4>([&](auto i) {
+        constexpr int I = decltype(i)::value * 4;
+        constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, I);
+        const float4 q = *reinterpret_cast<const float4*>(p + thread_elem + off);
+        r[I] = q.x * scale; r[I + 1] = q.y * scale; r[I + 2] = q.z * scale; r[I + 3] = q.w * scale;
+    });
+}
+
+template <class C>
+__device__ __forceinline__ float inv_sqrt_d() {
+    // exact power of two for even log2 d; one rounding of 1/sqrt(2) * 2^-k otherwise
+    return (C::n % 2 == 0) ? 1.0f / float(1 << (C::n / 2))
+                           : 0.70710678118654752440f / float(1 << (C::n / 2));
+}
+
+// ------------------------------------------------------------------------------------------------
+// forward:  y = (alpha / sqrt d) (.) (H_raw x) + beta
+
+template <class C>
+__global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::elem_t* x,
+                                                        const float* __restrict__ alpha,
+                                                        const float* __restrict__ beta,
+                                                        typename C::io::elem_t* y,
+                                                        int64_t N) {
+    extern __shared__ __align__(16) float lds[];
+    constexpr int LAST = C::P - 1;
+    const unsigned t = threadIdx.x % C::TPT, slot = threadIdx.x / C::TPT;
+    ThreadMap<C> tm;
+    tm.init(t, slot);
+
+    float a[C::E], b[C::E];
+    param_get<C, LAST>(a, alpha, tm.last_elem, inv_sqrt_d<C>());
+    param_get<C, LAST>(b, beta, tm.last_elem, 1.0f);
+
+    const int64_t groups = (N + C::G - 1) / C::G;
+    for (int64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+        const int64_t tok = grp * C::G + slot;
+        const bool active = tok < N;
+        float r[C::E];
+        global_get<C, 0>(r, x + tok * C::D, tm.first_elem, active);
+        transform<C, true>(r, lds, tm);
+#pragma unroll
+        for (int i = 0; i < C::E; ++i) r[i] = fmaf(r[i], a[i], b[i]);
+        global_put<C, LAST>(r, y + tok * C::D, tm.last_elem, active);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward:  z = H x (recomputed);  dalpha += dy z;  dbeta += dy;  dx = H_raw((alpha/sqrt d) dy)
+// Each workgroup walks a strided set of token groups, keeps its dalpha/dbeta sums in registers,
+// and at the end writes one row of partial sums; reduce_partials_kernel adds the rows in a fixed
+// order, so the result does not depend on scheduling.
+
+template <class C>
+__global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::elem_t* dy,
+                                                         const typename C::io::elem_t* x,
+                                                         const float* __restrict__ alpha,
+                                                         typename C::io::elem_t* dx,
+                                                         float* __restrict__ partials,   // [grid][2][D]
+                                                         int64_t N) {
+    extern __shared__ __align__(16) float lds[];
+    constexpr int LAST = C::P - 1;
+    const unsigned t = threadIdx.x % C::TPT, slot = threadIdx.x / C::TPT;
+    ThreadMap<C> tm;
+    tm.init(t, slot);
+
+    float a[C::E], da[C::E], db[C::E];
+    param_get<C, LAST>(a, alpha, tm.last_elem, inv_sqrt_d<C>());
+#pragma unroll
+    for (int i = 0; i < C::E; ++i) { da[i] = 0.0f; db[i] = 0.0f; }
+
+    const int64_t groups = (N + C::G - 1) / C::G;
+    for (int64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+        const int64_t tok = grp * C::G + slot;
+        const bool active = tok < N;
+        float r[C::E], g[C::E];
+        global_get<C, 0>(r, x + tok * C::D, tm.first_elem, active);
+        transform<C, true>(r, lds, tm);                       // r = H_raw x, last layout
+        global_get<C, LAST>(g, dy + tok * C::D, tm.last_elem, active);
+#pragma unroll
+        for (int i = 0; i < C::E; ++i) {
+            da[i] = fmaf(g[i], r[i], da[i]);                  // 1/sqrt d applied once at the end
+            db[i] += g[i];
+            g[i] *= a[i];
+        }
+        transform<C, false>(g, lds, tm);                      // g = H_raw(alpha' dy), first layout
+        global_put<C, 0>(g, dx + tok * C::D, tm.first_elem, active);
+    }
+
+    // Sum the G token slots of this workgroup through LDS, then write the workgroup's row.
+    const float s = inv_sqrt_d<C>();
+    float* row = partials + (size_t)blockIdx.x * 2 * C::D;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+        if constexpr (C::G == 1) {
+            static_for<0, C::E / 4>([&](auto i) {
+                constexpr int I = decltype(i)::value * 4;
+                constexpr unsigned off = reg_elem_offset(C::plan.ph[LAST], C::e, I);
+                const float4 q = which == 0 ? make_float4(da[I] * s, da[I + 1] * s, da[I + 2] * s, da[I + 3] * s)
+                                            : make_float4(db[I], db[I + 1], db[I + 2], db[I + 3]);
+                *reinterpret_cast<float4*>(row + which * C::D + tm.last_elem + off) = q;
+            });
+        } else {
+            if (which == 0) lds_put<C, LAST>(da, lds + tm.lds_off[LAST]);
+            else            lds_put<C, LAST>(db, lds + tm.lds_off[LAST]);
+            __syncthreads();
+            for (unsigned j = threadIdx.x; j < (unsigned)C::D; j += C::BT) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int gslot = 0; gslot < C::G; ++gslot) acc += lds[gslot * C::kTokenWords + lds_phys(j)];
+                row[which * C::D + j] = which == 0 ? acc * s : acc;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// out[which][j] = sum over rows of partials[row][which][j], rows added in index order.
+// Workgroup = 64 columns x 4 row lanes; the 4 lane sums are added in lane order.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partials,
+                                                              int rows, int d,
+                                                              float* __restrict__ dalpha,
+                                                              float* __restrict__ dbeta) {
+    __shared__ float part[4][64];
+    const int col = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int lane_row = threadIdx.x >> 6;
+    const int which = blockIdx.y;
+    float acc = 0.0f;
+    if (col < d)
+        for (int r = lane_row; r < rows; r += 4) acc += partials[((size_t)r * 2 + which) * d + col];
+    part[lane_row][threadIdx.x & 63] = acc;
+    __syncthreads();
+    if (lane_row == 0 && col < d) {
+        const int c = threadIdx.x & 63;
+        const float total = ((part[0][c] + part[1][c]) + part[2][c]) + part[3][c];
+        (which == 0 ? dalpha : dbeta)[col] = total;
+    }
+}
+
+__global__ void zero_kernel(float* a, float* b, int d) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < d) { a[i] = 0.0f; b[i] = 0.0f; }
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                   size_t nvec) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x * 4;
+    for (size_t base = ((size_t)blockIdx.x * blockDim.x) * 4 + threadIdx.x; base < nvec; base += stride) {
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (base + k * 256 < nvec) v[k] = src[base + k * 256];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (base + k * 256 < nvec) dst[base + k * 256] = v[k];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side: launch shapes and dispatch
+
+constexpr int kNumCU = 256;             // MI355X
+constexpr int kMaxGroupsPerCU = 4;      // resident workgroups per CU the grid is sized for
+
+template <class C>
+static int grid_for(int64_t N) {
+    const int64_t groups = (N + C::G - 1) / C::G;
+    const int64_t cap = (int64_t)kNumCU * kMaxGroupsPerCU;
+    return (int)(groups < cap ? groups : cap);
+}
+
+// Workgroups of the largest d need more than the 64 KiB of LDS a kernel may use by default.
+template <class C, class K>
+static bool allow_lds(K kernel) {
+    if constexpr (C::kLdsBytes > 64u * 1024u) {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)C::kLdsBytes) == hipSuccess;
+    }
+    return true;
+}
+
+template <class C>
+static int launch_forward(const void* x, const float* alpha, const float* beta, void* y, int64_t N,
+                          hipStream_t stream) {
+    using T = typename C::io::elem_t;
+    if (!allow_lds<C>(forward_kernel<C>)) return WHT_ERR_LAUNCH;
+    hipLaunchKernelGGL(forward_kernel<C>, dim3(grid_for<C>(N)), dim3(C::BT), C::kLdsBytes, stream,
+                       static_cast<const T*>(x), alpha, beta, static_cast<T*>(y), N);
+    return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
+}
+
+template <class C>
+static int launch_backward(const void* dy, const void* x, const float* alpha, void* dx, float* dalpha,
+                           float* dbeta, int64_t N, void* workspace, hipStream_t stream) {
+    using T = typename C::io::elem_t;
+    const int grid = grid_for<C>(N);
+    if (!allow_lds<C>(backward_kernel<C>)) return WHT_ERR_LAUNCH;
+    hipLaunchKernelGGL(backward_kernel<C>, dim3(grid), dim3(C::BT), C::kLdsBytes, stream,
+                       static_cast<const T*>(dy), static_cast<const T*>(x), alpha, static_cast<T*>(dx),
+                       static_cast<float*>(workspace), N);
+    if (hipGetLastError() != hipSuccess) return WHT_ERR_LAUNCH;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((C::D + 63) / 64, 2), dim3(256), 0, stream,
+                       static_cast<const float*>(workspace), grid, C::D, dalpha, dbeta);
+    return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
+}
+
+template <class C>
+static size_t workspace_for(int64_t N) { return (size_t)grid_for<C>(N) * 2 * C::D * sizeof(float); }
+
+enum class Op { Forward, Backward, Workspace };
+
+struct Args {
+    const void* x; const void* dy; const float* alpha; const float* beta;
+    void* y; void* dx; float* dalpha; float* dbeta;
+    int64_t N; void* workspace; hipStream_t stream;
+    size_t workspace_out;
+};
+
+template <class C>
+static int run(Op op, Args& a) {
+    switch (op) {
+    case Op::Forward:  return launch_forward<C>(a.x, a.alpha, a.beta, a.y, a.N, a.stream);
+    case Op::Backward: return launch_backward<C>(a.dy, a.x, a.alpha, a.dx, a.dalpha, a.dbeta, a.N,
+                                                 a.workspace, a.stream);
+    default:           a.workspace_out = workspace_for<C>(a.N); return WHT_OK;
+    }
+}
+
+template <class Io, int LOGD>
+static int run_d(Op op, Args& a) { return run<Cfg<LOGD, log_e_for(LOGD, Io::kLogVec), Io>>(op, a); }
+
+template <class Io>
+static int dispatch_d(int logd, Op op, Args& a) {
+    switch (logd) {
+    case 5:  return run_d<Io, 5>(op, a);
+    case 6:  return run_d<Io, 6>(op, a);
+    case 7:  return run_d<Io, 7>(op, a);
+    case 8:  return run_d<Io, 8>(op, a);
+    case 9:  return run_d<Io, 9>(op, a);
+    case 10: return run_d<Io, 10>(op, a);
+    case 11: return run_d<Io, 11>(op, a);
+    case 12: return run_d<Io, 12>(op, a);
+    case 13: return run_d<Io, 13>(op, a);
+    case 14: return run_d<Io, 14>(op, a);
+    default: return WHT_ERR_BAD_DIM;
+    }
+}
+
+static int dispatch(int logd, int dtype, Op op, Args& a) {
+    return dtype == WHT_DTYPE_F32 ? dispatch_d<IoF32>(logd, op, a) : dispatch_d<IoBF16>(logd, op, a);
+}
+
+static int log2_exact(int32_t d) {
+    if (d < WHT_MIN_D || d > WHT_MAX_D || (d & (d - 1)) != 0) return -1;
+    int l = 0;
+    while ((1 << l) < d) ++l;
+    return l;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int check_dims(int64_t N, int32_t d, int32_t dtype, int* logd) {
+    if (dtype != WHT_DTYPE_F32 && dtype != WHT_DTYPE_BF16) return WHT_ERR_BAD_DTYPE;
+    *logd = log2_exact(d);
+    if (*logd < 0 || N < 0) return WHT_ERR_BAD_DIM;
+    return WHT_OK;
+}
+
+}  // namespace wht
+
+// ------------------------------------------------------------------------------------------------
+// C ABI
+
+extern "C" {
+
+int wht_affine_forward(const void* x, const float* alpha, const float* beta, void* y, int64_t N,
+                       int32_t d, int32_t dtype, void* stream) {
+    using namespace wht;
+    if (!x || !alpha || !beta || !y) return WHT_ERR_NULL_PTR;
+    int logd = 0;
+    if (int rc = check_dims(N, d, dtype, &logd)) return rc;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(alpha) || !aligned16(beta)) return WHT_ERR_MISALIGNED;
+    if (N == 0) return WHT_OK;
+    Args a{};
+    a.x = x; a.alpha = alpha; a.beta = beta; a.y = y; a.N = N;
+    a.stream = static_cast<hipStream_t>(stream);
+    return dispatch(logd, dtype, Op::Forward, a);
+}
+
+size_t wht_affine_backward_workspace_bytes(int64_t N, int32_t d, int32_t dtype) {
+    using namespace wht;
+    int logd = 0;
+    if (check_dims(N, d, dtype, &logd) != WHT_OK || N == 0) return 0;
+    Args a{};
+    a.N = N;
+    dispatch(logd, dtype, Op::Workspace, a);
+    return a.workspace_out;
+}
+
+int wht_affine_backward(const void* dy, const void* x, const float* alpha, void* dx, float* dalpha,
+                        float* dbeta, int64_t N, int32_t d, int32_t dtype, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+    using namespace wht;
+    if (!dy || !x || !alpha || !dx || !dalpha || !dbeta) return WHT_ERR_NULL_PTR;
+    int logd = 0;
+    if (int rc = check_dims(N, d, dtype, &logd)) return rc;
+    if (!aligned16(dy) || !aligned16(x) || !aligned16(alpha) || !aligned16(dx) || !aligned16(dalpha) ||
+        !aligned16(dbeta))
+        return WHT_ERR_MISALIGNED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (N == 0) {
+        hipLaunchKernelGGL(zero_kernel, dim3((d + 255) / 256), dim3(256), 0, s, dalpha, dbeta, d);
+        return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
+    }
+    const size_t need = wht_affine_backward_workspace_bytes(N, d, dtype);
+    if (!workspace || workspace_bytes < need) return WHT_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return WHT_ERR_MISALIGNED;
+    Args a{};
+    a.dy = dy; a.x = x; a.alpha = alpha; a.dx = dx; a.dalpha = dalpha; a.dbeta = dbeta; a.N = N;
+    a.workspace = workspace; a.stream = s;
+    return dispatch(logd, dtype, Op::Backward, a);
+}
+
+int wht_affine_copy_baseline(const void* src, void* dst, size_t bytes, void* stream) {
+    using namespace wht;
+    if (!src || !dst) return WHT_ERR_NULL_PTR;
+    if (bytes % 16 != 0) return WHT_ERR_BAD_DIM;
+    if (!aligned16(src) || !aligned16(dst)) return WHT_ERR_MISALIGNED;
+    if (bytes == 0) return WHT_OK;
+    const size_t nvec = bytes / 16;
+    const size_t want = (nvec + 1023) / 1024;
+    const int grid = (int)(want < (size_t)kNumCU * 8 ? want : (size_t)kNumCU * 8);
+    hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4*>(src), static_cast<uint4*>(dst), nvec);
+    return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
+}
+
+const char* wht_affine_status_string(int status) {
+    switch (status) {
+    case WHT_OK:             return "ok";
+    case WHT_ERR_NULL_PTR:   return "a required pointer is NULL";
+    case WHT_ERR_BAD_DIM:    return "d must be a power of two in [WHT_MIN_D, WHT_MAX_D] and N >= 0";
+    case WHT_ERR_BAD_DTYPE:  return "dtype must be WHT_DTYPE_F32 or WHT_DTYPE_BF16";
+    case WHT_ERR_MISALIGNED: return "tensor pointers must be 16-byte aligned";
+    case WHT_ERR_WORKSPACE:  return "workspace is NULL or smaller than wht_affine_backward_workspace_bytes";
+    case WHT_ERR_LAUNCH:     return "the HIP runtime refused a kernel launch";
+    default:                 return "unknown status";
+    }
+}
+
+int wht_affine_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,144 @@
+// Compile-time schedule of one token's fast Walsh-Hadamard transform across a group of threads.
+//
+// A token has d = 2^n elements.  It is held by 2^(n-e) threads, 2^e values per thread, in float32
+// registers.  A butterfly stage on element-index bit b (paper Fig. 2: pairs whose indices differ by
+// the stride 2^b) costs one add or subtract per element when bit b is a bit of the *register*
+// index, so the schedule is a short list of layouts ("phases"); each phase names which e element
+// bits are register-resident, the stages run on those, and between phases the token is re-dealt
+// through LDS.  Stages commute (they act on different index bits), so any order gives H_raw x.
+//
+// The first and the last layout keep element bits 0..v-1 in registers (2^v elements = one 16-byte
+// global vector) and give the lowest thread bits the next element bits, so that global loads and
+// stores are 16 bytes per lane and contiguous across lanes.
+#pragma once
+
+namespace wht {
+
+constexpr int kMaxRegBits = 6;
+constexpr int kMaxBits = 16;
+constexpr int kMaxPhases = 5;
+
+struct PhaseDesc {
+    int rb[kMaxRegBits];   // rb[q]: element-index bit carried by bit q of the register index
+    int tb[kMaxBits];      // tb[k]: element-index bit carried by bit k of the thread index
+    unsigned stages;       // element bits butterflied while the token is in this layout
+};
+
+struct PlanDesc {
+    int n, e, v, nphase;
+    PhaseDesc ph[kMaxPhases];
+};
+
+constexpr int popcount_u(unsigned m) { int c = 0; while (m) { c += m & 1u; m >>= 1; } return c; }
+constexpr int lowest_bit(unsigned m) { int b = 0; while (!(m & 1u)) { m >>= 1; ++b; } return b; }
+
+constexpr unsigned reg_mask(const PhaseDesc& p, int e) {
+    unsigned m = 0;
+    for (int q = 0; q < e; ++q) m |= 1u << p.rb[q];
+    return m;
+}
+
+constexpr void fill_thread_bits(PhaseDesc& p, int n, int e) {
+    const unsigned inreg = reg_mask(p, e);
+    int k = 0;
+    for (int b = 0; b < n; ++b)
+        if (!((inreg >> b) & 1u)) p.tb[k++] = b;
+    for (; k < kMaxBits; ++k) p.tb[k] = 0;
+}
+
+// log2(values per thread) the library uses for a given log2 d: 32 values where the token is large
+// enough to keep 8 threads busy, never fewer than one 16-byte vector.
+constexpr int log_e_for(int logd, int logv) {
+    int e = logd - 3;
+    if (e > 5) e = 5;
+    if (e < logv) e = logv;
+    return e;
+}
+
+// n = log2 d, e = log2(values per thread), v = log2(elements per 16-byte vector);  v <= e <= n.
+constexpr PlanDesc make_plan(int n, int e, int v) {
+    PlanDesc pl{};
+    pl.n = n; pl.e = e; pl.v = v; pl.nphase = 0;
+    const unsigned all = (1u << n) - 1u;
+    unsigned undone = all;
+
+    // first phase: the vector bits and the top e-v bits
+    PhaseDesc first{};
+    for (int q = 0; q < v; ++q) first.rb[q] = q;
+    for (int q = v; q < e; ++q) first.rb[q] = n - (e - v) + (q - v);
+    first.stages = reg_mask(first, e);
+    fill_thread_bits(first, n, e);
+    undone &= ~first.stages;
+    pl.ph[pl.nphase++] = first;
+    if (n == e) return pl;
+
+    // the last phase can take e-v new bits: reserve the top ones still undone for it -- but only
+    // bits >= v+3, so that its three lowest thread bits stay element bits v..v+2 (eight lanes
+    // cover 128 contiguous bytes of the global store)
+    unsigned reserved = 0;
+    {
+        int taken = 0;
+        for (int b = n - 1; b >= v + 3 && taken < e - v; --b)
+            if ((undone >> b) & 1u) { reserved |= 1u << b; ++taken; }
+    }
+    // middle phases: windows of e consecutive element bits, lowest undone bit first
+    unsigned middle = undone & ~reserved;
+    while (middle) {
+        int lo = lowest_bit(middle);
+        if (lo > n - e) lo = n - e;
+        PhaseDesc mid{};
+        for (int q = 0; q < e; ++q) mid.rb[q] = lo + q;
+        mid.stages = reg_mask(mid, e) & undone;
+        fill_thread_bits(mid, n, e);
+        undone &= ~mid.stages;
+        middle &= ~mid.stages;
+        pl.ph[pl.nphase++] = mid;
+    }
+    // last phase: vector bits, whatever is still undone, then top bits to fill the register index
+    PhaseDesc last{};
+    for (int q = 0; q < v; ++q) last.rb[q] = q;
+    {
+        int q = v;
+        unsigned used = (1u << v) - 1u;
+        for (int b = 0; b < n && q < e; ++b)
+            if ((undone >> b) & 1u) { last.rb[q++] = b; used |= 1u << b; }
+        for (int b = n - 1; b >= 0 && q < e; --b)
+            if (!((used >> b) & 1u)) { last.rb[q++] = b; used |= 1u << b; }
+        // keep the chunk bits ascending so register order follows memory order
+        for (int i = v; i < e; ++i)
+            for (int j = i + 1; j < e; ++j)
+                if (last.rb[j] < last.rb[i]) { int t = last.rb[i]; last.rb[i] = last.rb[j]; last.rb[j] = t; }
+    }
+    last.stages = undone;
+    fill_thread_bits(last, n, e);
+    pl.ph[pl.nphase++] = last;
+    return pl;
+}
+
+// Element offset contributed by register index r in a phase.
+constexpr unsigned reg_elem_offset(const PhaseDesc& p, int e, int r) {
+    unsigned off = 0;
+    for (int q = 0; q < e; ++q)
+        if ((r >> q) & 1) off |= 1u << p.rb[q];
+    return off;
+}
+
+// Every element bit must be butterflied exactly once over the phases.
+constexpr bool plan_is_complete(const PlanDesc& pl) {
+    unsigned seen = 0;
+    for (int p = 0; p < pl.nphase; ++p) {
+        if (seen & pl.ph[p].stages) return false;
+        if (pl.ph[p].stages & ~reg_mask(pl.ph[p], pl.e)) return false;
+        seen |= pl.ph[p].stages;
+    }
+    return seen == (1u << pl.n) - 1u;
+}
+
+// LDS word address of element i of a token.  Two skews, both multiples of 4 words so that four
+// consecutive elements stay one aligned 16-byte access: +4 words every 64 elements keeps the
+// 16-byte-per-lane accesses of the first/last layouts off each other's banks, +8 words every 256
+// elements does the same for the one-word accesses of the middle layouts (lanes 256 elements apart).
+// Linear in the bits of i, so phys(a | b) = phys(a) + phys(b) for disjoint a, b.
+constexpr unsigned lds_phys(unsigned i) { return i + ((i >> 6) << 2) + ((i >> 8) << 3); }
+
+}  // namespace wht

@@ -1,0 +1,269 @@
+"""GPU parity: the HIP kernels, called through the C ABI, against the CPU oracle on identical
+seeded inputs.  Element by element at sizes the oracle finishes in seconds (several workgroup
+passes and a ragged tail), and at the benchmark's full sizes on sampled tokens (y, dx: every token
+is independent, so a sample is checked exactly) plus the full dalpha/dbeta reductions."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2603_08343_amd as wht
+from paper_2603_08343_amd import binding, synth
+from parity import assert_grad_close, assert_io_close, to_f64, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _announce(msg):
+    print(f"[parity] {msg}", flush=True)
+
+
+def _method(d):
+    return "matrix" if d <= 512 else "fast"
+
+
+def run_forward(inp):
+    x = to_gpu(inp.x, inp.dtype)
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    y = wht.wht_affine_forward(x, a, b)
+    torch.cuda.synchronize()
+    return y
+
+
+def run_backward(inp):
+    x, dy = to_gpu(inp.x, inp.dtype), to_gpu(inp.dy, inp.dtype)
+    a = torch.from_numpy(inp.alpha).cuda()
+    out = wht.wht_affine_backward(dy, x, a)
+    torch.cuda.synchronize()
+    return out
+
+
+def check_forward_full(inp, what):
+    y = run_forward(inp)
+    ref = oracle.forward(inp.x, inp.alpha, inp.beta, _method(inp.d))
+    assert_io_close(y, ref.reshape(inp.N, inp.d), inp.dtype, f"{what} y")
+
+
+def check_backward_full(inp, what):
+    dx, da, db = run_backward(inp)
+    rdx, rda, rdb = oracle.backward(inp.dy, inp.x, inp.alpha, _method(inp.d))
+    assert_io_close(dx, rdx.reshape(inp.N, inp.d), inp.dtype, f"{what} dx")
+    assert_grad_close(da, rda, f"{what} dalpha")
+    assert_grad_close(db, rdb, f"{what} dbeta")
+
+
+ALL_D = [32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d", ALL_D)
+def test_forward_every_d(d, dtype):
+    # N chosen so that the last workgroup pass is ragged for every tokens-per-workgroup value
+    N = 67 if d <= 2048 else 9
+    _announce(f"forward d={d} {dtype} N={N}")
+    check_forward_full(synth.make_inputs(N, d, dtype, seed=d, backward=False), f"fwd d={d} {dtype}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d", ALL_D)
+def test_backward_every_d(d, dtype):
+    N = 67 if d <= 2048 else 9
+    _announce(f"backward d={d} {dtype} N={N}")
+    check_backward_full(synth.make_inputs(N, d, dtype, seed=d + 1), f"bwd d={d} {dtype}")
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 127, 128, 129, 1031])
+@pytest.mark.parametrize("d,dtype", [(256, "f32"), (1024, "bf16"), (8192, "bf16")])
+def test_reduction_over_odd_token_counts(N, d, dtype):
+    if d == 8192 and N > 129:
+        N = 257
+    _announce(f"reduction N={N} d={d} {dtype}")
+    check_backward_full(synth.make_inputs(N, d, dtype, seed=N), f"bwd N={N} d={d}")
+
+
+def test_many_passes_per_workgroup():
+    # more token groups than the grid cap: every workgroup loops several times, last pass ragged
+    inp = synth.make_inputs(5000, 256, "bf16", seed=3)
+    _announce("grid-stride d=256 N=5000 (tokens per workgroup 32, 157 groups)")
+    check_forward_full(inp, "fwd strided")
+    inp2 = synth.make_inputs(40001, 64, "f32", seed=4)
+    _announce("grid-stride d=64 N=40001")
+    check_forward_full(inp2, "fwd strided d=64")
+    check_backward_full(inp2, "bwd strided d=64")
+
+
+# ------------------------------------------------------------------ the benchmark configurations
+
+def test_config_C1_tiny():
+    inp = synth.make_workload("C1_tiny")
+    _announce("C1 tiny N=64 d=256 f32")
+    check_forward_full(inp, "C1")
+    # the definition itself, not only the butterfly oracle
+    y = run_forward(inp)
+    assert_io_close(y, oracle.forward(inp.x, inp.alpha, inp.beta, "matrix"), "f32", "C1 vs matrix")
+
+
+@pytest.mark.parametrize("N", [1, 16, 64, 256])
+def test_config_C4_decode(N):
+    inp = synth.make_workload(f"C4_decode_n{N}")
+    _announce(f"C4 decode N={N} d=4096 bf16")
+    check_forward_full(inp, f"C4 N={N}")
+
+
+def _sample_tokens(N, count, seed):
+    rng = np.random.default_rng(seed)
+    idx = np.unique(np.concatenate([[0, 1, N // 2, N - 2, N - 1], rng.integers(0, N, size=count)]))
+    return idx
+
+
+def _full_size(name, check_bwd):
+    w = synth.WORKLOADS[name]
+    _announce(f"{name} full size N={w.N} d={w.d} {w.dtype}: generating inputs")
+    inp = synth.make_workload(name)
+    idx = _sample_tokens(w.N, 48, seed=w.d)
+    _announce(f"{name}: forward on GPU")
+    y = run_forward(inp)
+    ref_y = oracle.forward(inp.x[idx], inp.alpha, inp.beta, "fast")
+    assert_io_close(y[torch.from_numpy(idx).cuda()], ref_y, inp.dtype, f"{name} y (sampled tokens)")
+    # a few tokens against the O(d^2) definition as well
+    few = idx[:6]
+    assert_io_close(y[torch.from_numpy(few).cuda()], oracle.forward(inp.x[few], inp.alpha, inp.beta, "matrix"),
+                    inp.dtype, f"{name} y (definition)")
+    # every output finite and written (no token skipped): the oracle-independent property that
+    # sum_j (y - beta)^2 / alpha^2 = ||x||^2 per token is checked loosely on all tokens
+    yf = y.float()
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    z2 = (((yf - b) / a) ** 2).sum(dim=1)
+    xt = to_gpu(inp.x, inp.dtype).float()
+    x2 = (xt ** 2).sum(dim=1)
+    assert torch.all(torch.isfinite(yf))
+    assert float(((z2 - x2).abs() / x2).max()) < 2e-2, f"{name}: norm preservation violated on some token"
+    del y, yf, xt, z2, x2
+    if not check_bwd:
+        return
+    _announce(f"{name}: backward on GPU")
+    dx, da, db = run_backward(inp)
+    _announce(f"{name}: oracle dalpha/dbeta over all {w.N} tokens")
+    _, rda, rdb = oracle.backward(inp.dy, inp.x, inp.alpha, "fast", want_dx=False)
+    assert_grad_close(da, rda, f"{name} dalpha")
+    assert_grad_close(db, rdb, f"{name} dbeta")
+    rdx, _, _ = oracle.backward(inp.dy[idx], inp.x[idx], inp.alpha, "fast", want_param_grads=False)
+    assert_io_close(dx[torch.from_numpy(idx).cuda()], rdx, inp.dtype, f"{name} dx (sampled tokens)")
+    assert torch.all(torch.isfinite(dx.float()))
+
+
+def test_config_C2_training_full_size():
+    _full_size("C2_train", True)
+
+
+def test_config_C3_prefill_full_size_with_outliers():
+    _full_size("C3_prefill", False)
+
+
+def test_config_C4b_roofline_shape_full_size():
+    _full_size("C4b_roofline", True)
+
+
+def test_config_C5_large_full_size():
+    _full_size("C5_large", True)
+
+
+# ------------------------------------------------------------------ edge cases and the boundary
+
+def test_special_inputs():
+    d, N = 1024, 5
+    ones, zeros = torch.ones(d, device="cuda"), torch.zeros(d, device="cuda")
+    inp = synth.make_inputs(N, d, "f32", seed=9, backward=False)
+    x = to_gpu(inp.x, "f32")
+    # alpha = 1, beta = 0: y = Hx, and applying the layer twice returns x (H is an involution)
+    z = wht.wht_affine_forward(x, ones, zeros)
+    back = wht.wht_affine_forward(z, ones, zeros)
+    torch.cuda.synchronize()
+    assert float((back - x).abs().max()) <= 1e-5 * float(x.abs().max())
+    # x = 0: y = beta exactly
+    b = torch.from_numpy(inp.beta).cuda()
+    y0 = wht.wht_affine_forward(torch.zeros(N, d, device="cuda"), torch.from_numpy(inp.alpha).cuda(), b)
+    assert torch.equal(y0, b.expand(N, d))
+    # unit vector: y = alpha * column k of H + beta
+    k = 37
+    e = torch.zeros(1, d, device="cuda")
+    e[0, k] = 1.0
+    ye = wht.wht_affine_forward(e, torch.from_numpy(inp.alpha).cuda(), b)
+    ref = oracle.forward(e.cpu().numpy(), inp.alpha, inp.beta, "matrix")
+    assert_io_close(ye, ref, "f32", "unit vector")
+
+
+def test_in_place_and_preallocated_outputs():
+    inp = synth.make_inputs(33, 2048, "bf16", seed=11)
+    x, dy = to_gpu(inp.x, "bf16"), to_gpu(inp.dy, "bf16")
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    y_ref = wht.wht_affine_forward(x, a, b)
+    x2 = x.clone()
+    wht.wht_affine_forward(x2, a, b, y=x2)                       # y aliases x exactly
+    dx_ref, da_ref, db_ref = wht.wht_affine_backward(dy, x, a)
+    dy2 = dy.clone()
+    dx2, da2, db2 = wht.wht_affine_backward(dy2, x, a, dx=dy2)   # dx aliases dy exactly
+    torch.cuda.synchronize()
+    assert torch.equal(x2.view(torch.int16), y_ref.view(torch.int16))
+    assert torch.equal(dx2.view(torch.int16), dx_ref.view(torch.int16))
+    assert torch.equal(da2, da_ref) and torch.equal(db2, db_ref)
+
+
+def test_backward_is_bit_reproducible():
+    inp = synth.make_inputs(4099, 1024, "bf16", seed=13)
+    first = run_backward(inp)
+    second = run_backward(inp)
+    assert torch.equal(first[1], second[1]) and torch.equal(first[2], second[2])
+    assert torch.equal(first[0].view(torch.int16), second[0].view(torch.int16))
+
+
+def test_zero_tokens():
+    d = 512
+    a = torch.ones(d, device="cuda")
+    x = torch.empty(0, d, device="cuda", dtype=torch.bfloat16)
+    y = wht.wht_affine_forward(x, a, a)
+    assert y.shape == (0, d)
+    da = torch.full((d,), 7.0, device="cuda")
+    db = torch.full((d,), 7.0, device="cuda")
+    wht.wht_affine_backward(x, x, a, dalpha=da, dbeta=db)
+    torch.cuda.synchronize()
+    assert float(da.abs().max()) == 0.0 and float(db.abs().max()) == 0.0
+
+
+def test_non_default_stream():
+    inp = synth.make_inputs(300, 4096, "bf16", seed=17, backward=False)
+    x = to_gpu(inp.x, "bf16")
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        y = wht.wht_affine_forward(x, a, b)
+    s.synchronize()
+    ref = oracle.forward(inp.x, inp.alpha, inp.beta, "fast")
+    assert_io_close(y, ref, "bf16", "side stream")
+
+
+def test_boundary_errors_on_gpu():
+    d, N = 256, 4
+    x = torch.zeros(N, d, device="cuda")
+    a = torch.ones(d, device="cuda")
+    ws = torch.empty(64, dtype=torch.uint8, device="cuda")
+    before_da = torch.full((d,), 3.0, device="cuda")
+    rc = binding.wht_affine_backward_raw(x.data_ptr(), x.data_ptr(), a.data_ptr(), x.data_ptr(),
+                                         before_da.data_ptr(), before_da.data_ptr(), N, d, 0,
+                                         ws.data_ptr(), 64)
+    assert rc == 5                                                # WHT_ERR_WORKSPACE, nothing enqueued
+    torch.cuda.synchronize()
+    assert float(before_da.min()) == 3.0
+    assert binding.wht_affine_forward_raw(x.data_ptr() + 4, a.data_ptr(), a.data_ptr(), x.data_ptr(), N, d, 0) == 4
+    with pytest.raises(wht.WhtAffineError):
+        wht.wht_affine_forward(torch.zeros(2, 768, device="cuda"), torch.ones(768, device="cuda"),
+                               torch.ones(768, device="cuda"))
+
+
+def test_copy_baseline_copies():
+    src = torch.randint(-2 ** 31, 2 ** 31 - 1, (1 << 20) + 4, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    wht.wht_affine_copy_baseline(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)

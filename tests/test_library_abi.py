@@ -1,0 +1,102 @@
+"""CPU-side checks of the boundary: the shared library loads, exports every symbol the header
+declares, and rejects bad arguments before touching the GPU (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_08343_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "wht_affine.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(wht_affine_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(binding.library_path())
+    names = _declared_functions()
+    assert len(names) >= 6
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in wht_affine.h but not exported"
+    assert set(binding.EXPORTS) == set(names)
+
+
+def test_version_and_status_strings():
+    assert binding.wht_affine_version() >= 100
+    seen = {binding.wht_affine_status_string(s) for s in range(0, 7)}
+    assert len(seen) == 7 and "ok" in seen
+    assert binding.wht_affine_status_string(99) == "unknown status"
+
+
+OK, NULLP, DIM, DTYPE, ALIGN, WS = 0, 1, 2, 3, 4, 5
+P = 0x1000   # a 16-byte-aligned non-null fake address: validation fails before it is ever used
+
+
+@pytest.mark.parametrize("args,want", [
+    ((0, P, P, P, 4, 256, 0), NULLP),
+    ((P, 0, P, P, 4, 256, 0), NULLP),
+    ((P, P, 0, P, 4, 256, 0), NULLP),
+    ((P, P, P, 0, 4, 256, 0), NULLP),
+    ((P, P, P, P, 4, 768, 1), DIM),        # the paper's own non-power-of-two width: rejected
+    ((P, P, P, P, 4, 1536, 1), DIM),
+    ((P, P, P, P, 4, 16, 0), DIM),         # below WHT_MIN_D
+    ((P, P, P, P, 4, 32768, 0), DIM),      # above WHT_MAX_D
+    ((P, P, P, P, 4, 0, 0), DIM),
+    ((P, P, P, P, 4, -256, 0), DIM),
+    ((P, P, P, P, -1, 256, 0), DIM),
+    ((P, P, P, P, 4, 256, 2), DTYPE),
+    ((P, P, P, P, 4, 256, -1), DTYPE),
+    ((P + 8, P, P, P, 4, 256, 0), ALIGN),
+    ((P, P + 4, P, P, 4, 256, 0), ALIGN),
+    ((P, P, P, P + 2, 4, 256, 1), ALIGN),
+    ((P, P, P, P, 0, 256, 1), OK),         # N = 0: nothing to do, nothing enqueued
+])
+def test_forward_argument_validation(args, want):
+    assert binding.wht_affine_forward_raw(*args) == want
+
+
+def test_backward_argument_validation():
+    ws = binding.wht_affine_backward_workspace_bytes(100, 1024, 1)
+    assert ws > 0 and ws % 16 == 0
+    call = binding.wht_affine_backward_raw
+    assert call(0, P, P, P, P, P, 100, 1024, 1, P, ws) == NULLP
+    assert call(P, P, P, P, 0, P, 100, 1024, 1, P, ws) == NULLP
+    assert call(P, P, P, P, P, P, 100, 1000, 1, P, ws) == DIM
+    assert call(P, P, P, P, P, P, 100, 1024, 5, P, ws) == DTYPE
+    assert call(P, P + 1, P, P, P, P, 100, 1024, 1, P, ws) == ALIGN
+    assert call(P, P, P, P, P, P, 100, 1024, 1, 0, ws) == WS
+    assert call(P, P, P, P, P, P, 100, 1024, 1, P, ws - 1) == WS
+    assert call(P, P, P, P, P, P, 100, 1024, 1, P + 4, ws) == ALIGN
+
+
+def test_workspace_query():
+    q = binding.wht_affine_backward_workspace_bytes
+    assert q(0, 1024, 1) == 0
+    assert q(10, 1000, 1) == 0 and q(10, 1024, 9) == 0
+    # one row of 2*d floats per workgroup; never more workgroups than token groups
+    assert q(1, 8192, 1) == 2 * 8192 * 4
+    assert q(32768, 8192, 1) >= q(64, 8192, 1) > 0
+    assert q(32768, 8192, 1) <= 64 << 20
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libwht_affine.so")
+    with pytest.raises(RuntimeError, match="no CPU or eager fallback"):
+        binding.library()
+
+
+def test_product_path_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2603_08343_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "wht_oracle" not in text, f
