@@ -1,0 +1,303 @@
+#!/usr/bin/env python3
+"""Benchmark of the Walsh-Hadamard output layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-extras]
+
+One "step" is one pass of the whole hot path over one batch: wht_affine_forward followed by
+wht_affine_backward (forward only for forward-only workloads), inputs resident in HBM.  The last
+line printed is one JSON object: whole-job tokens/s, the HBM-roofline figure of the dominant kernel
+(measured here with events on the launch stream), and the CPU oracle timed on this host's cores on
+a bounded sample of the same workload.  Extra keys carry the other workloads, the plain-copy
+ceiling and the same-shape dense W_O GEMM.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C5_large")
+    ap.add_argument("--no-extras", action="store_true", help="headline workload only")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def io_bytes(dtype):
+    return 2 if dtype == "bf16" else 4
+
+
+def algorithmic_bytes(N, d, dtype, which):
+    """HBM bytes the method itself must move per launch: forward reads x and writes y (+ alpha,
+    beta); backward reads x, dy, writes dx (+ alpha read, dalpha/dbeta written)."""
+    s = io_bytes(dtype)
+    if which == "fwd":
+        return 2 * N * d * s + 8 * d
+    return 3 * N * d * s + 12 * d
+
+
+class Bench:
+    def __init__(self, torch, wht, synth, name, sets=None):
+        import numpy as np
+        self.torch, self.wht = torch, wht
+        w = synth.WORKLOADS[name]
+        self.w = w
+        tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        per_set = (4 if w.backward else 2) * w.N * w.d * io_bytes(w.dtype)
+        # rotate buffer sets so that consecutive steps cannot be served by the 256 MB Infinity Cache
+        self.sets = sets if sets is not None else max(1, min(8, -(-(1 << 30) // per_set)))
+        g = torch.Generator(device="cuda").manual_seed(0)
+        rng = np.random.Generator(np.random.PCG64(0))
+        self.alpha = torch.from_numpy(rng.uniform(0.5, 1.5, w.d).astype(np.float32)).cuda()
+        self.beta = torch.from_numpy((0.02 * rng.standard_normal(w.d)).astype(np.float32)).cuda()
+        self.x, self.dy, self.y, self.dx = [], [], [], []
+        for _ in range(self.sets):
+            x = torch.randn(w.N, w.d, device="cuda", dtype=torch.float32, generator=g)
+            if w.outliers:
+                mask = torch.rand(w.N, w.d, device="cuda", generator=g) < 0.01
+                x = torch.where(mask, x * 20.0, x)
+            self.x.append(x.to(tdt))
+            self.y.append(torch.empty(w.N, w.d, device="cuda", dtype=tdt))
+            if w.backward:
+                self.dy.append(torch.randn(w.N, w.d, device="cuda", dtype=torch.float32, generator=g).to(tdt))
+                self.dx.append(torch.empty(w.N, w.d, device="cuda", dtype=tdt))
+            del x
+        self.dalpha = torch.empty(w.d, device="cuda")
+        self.dbeta = torch.empty(w.d, device="cuda")
+        code = wht.DTYPE_BF16 if w.dtype == "bf16" else wht.DTYPE_F32
+        need = wht.wht_affine_backward_workspace_bytes(w.N, w.d, code) if w.backward else 0
+        self.ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+    def fwd(self, i):
+        k = i % self.sets
+        self.wht.wht_affine_forward(self.x[k], self.alpha, self.beta, y=self.y[k])
+
+    def bwd(self, i):
+        k = i % self.sets
+        self.wht.wht_affine_backward(self.dy[k], self.x[k], self.alpha, dx=self.dx[k], dalpha=self.dalpha,
+                                     dbeta=self.dbeta, workspace=self.ws)
+
+    def run(self, steps, warmup):
+        """Times `steps` whole steps (wall clock between synchronisations) and, inside the same
+        region, every forward and backward launch with events on the launch stream."""
+        torch = self.torch
+        for i in range(warmup):
+            self.fwd(i)
+            if self.w.backward:
+                self.bwd(i)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            ev[i][0].record()
+            self.fwd(i)
+            ev[i][1].record()
+            if self.w.backward:
+                self.bwd(i)
+                ev[i][2].record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+        bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps if self.w.backward else None
+        return (t1 - t0) * 1e3 / steps, fwd_ms, bwd_ms
+
+
+def summarize(w, step_ms, fwd_ms, bwd_ms):
+    out = {
+        "workload": w.name, "N": w.N, "d": w.d, "io_dtype": w.dtype,
+        "ms_per_step": round(step_ms, 5),
+        "tokens_per_s": w.N / (step_ms * 1e-3),
+        "fwd_ms": round(fwd_ms, 5),
+        "fwd_tokens_per_s": w.N / (fwd_ms * 1e-3),
+        "fwd_GBs": algorithmic_bytes(w.N, w.d, w.dtype, "fwd") / (fwd_ms * 1e-3) / 1e9,
+    }
+    out["fwd_frac_hbm_peak"] = out["fwd_GBs"] / HBM_PEAK_GBS
+    if bwd_ms is not None:
+        out["bwd_ms"] = round(bwd_ms, 5)
+        out["bwd_GBs"] = algorithmic_bytes(w.N, w.d, w.dtype, "bwd") / (bwd_ms * 1e-3) / 1e9
+        out["bwd_frac_hbm_peak"] = out["bwd_GBs"] / HBM_PEAK_GBS
+    return out
+
+
+def copy_ceiling(torch, wht, nbytes=1 << 30, iters=20):
+    src = [torch.empty(nbytes, dtype=torch.uint8, device="cuda").random_(0, 255) for _ in range(2)]
+    dst = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    for i in range(3):
+        wht.wht_affine_copy_baseline(src[i % 2], dst[i % 2])
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for i in range(iters):
+        wht.wht_affine_copy_baseline(src[i % 2], dst[i % 2])
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / iters
+    return {"bytes_moved": 2 * nbytes, "ms": ms, "GBs": 2 * nbytes / (ms * 1e-3) / 1e9}
+
+
+def dense_wo(torch, w, iters=10):
+    """Same-shape dense output projection on the same GPU (hipBLASLt through torch.matmul):
+    forward y = x W^T + b; backward dx = dy W, dW = dy^T x, db = sum dy."""
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    x = torch.randn(w.N, w.d, device="cuda", dtype=tdt)
+    W = torch.randn(w.d, w.d, device="cuda", dtype=tdt) / (w.d ** 0.5)
+    b = torch.zeros(w.d, device="cuda", dtype=tdt)
+    dy = torch.randn(w.N, w.d, device="cuda", dtype=tdt) if w.backward else None
+
+    def fwd():
+        return torch.addmm(b, x, W.t())
+
+    def bwd():
+        return dy @ W, dy.t() @ x, dy.sum(dim=0)
+
+    def timeit(fn):
+        for _ in range(2):
+            fn()
+        a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(iters):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(e) / iters
+
+    out = {"fwd_ms": timeit(fwd), "fwd_flops": 2.0 * w.N * w.d * w.d}
+    out["fwd_TFLOPs"] = out["fwd_flops"] / (out["fwd_ms"] * 1e-3) / 1e12
+    if w.backward:
+        out["bwd_ms"] = timeit(bwd)
+        out["fwd_bwd_ms"] = out["fwd_ms"] + out["bwd_ms"]
+    return out
+
+
+def cpu_baseline(synth, w, target_seconds):
+    """The CPU oracle as it stands (butterfly path, OpenMP over tokens), on a bounded sample of the
+    same workload: the first n tokens of the seeded recipe, passes repeated until about
+    `target_seconds` of oracle time has been spent; the mean pass time is reported."""
+    import oracle
+
+    n = min(w.N, 4096)
+    inp = synth.make_inputs(n, w.d, w.dtype, seed=0, backward=w.backward, outliers=w.outliers)
+
+    def one():
+        t0 = time.perf_counter()
+        oracle.forward(inp.x, inp.alpha, inp.beta, "fast")
+        if w.backward:
+            oracle.backward(inp.dy, inp.x, inp.alpha, "fast")
+        return time.perf_counter() - t0
+
+    one()                                                 # first call loads the library
+    spent, passes = 0.0, 0
+    while spent < target_seconds and passes < 200:
+        spent += one()
+        passes += 1
+    secs = spent / passes
+    return {"value": n / secs, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {n} of {w.N} tokens of {w.name} (d={w.d}, {w.dtype} inputs, "
+                      f"{'forward+backward' if w.backward else 'forward'}), fp64 butterfly oracle, "
+                      f"mean of {passes} passes, {spent:.1f} s of CPU time in total"}
+
+
+def decode_latency(torch, wht, synth, iters=1000):
+    """Per-call time of the decode shapes (one new token per sequence, d = 4096): back-to-back
+    launches, and the same-shape dense GEMV/GEMM."""
+    rows = []
+    for name in ("C4_decode_n1", "C4_decode_n16", "C4_decode_n64", "C4_decode_n256"):
+        w = synth.WORKLOADS[name]
+        b = Bench(torch, wht, synth, name, sets=1)
+        for i in range(20):
+            b.fwd(i)
+        a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(iters):
+            b.fwd(i)
+        e.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(e) * 1e3 / iters
+        dense = dense_wo(torch, w, iters=200)
+        rows.append({"N": w.N, "d": w.d, "wht_affine_us_per_call": us, "dense_wo_us_per_call": dense["fwd_ms"] * 1e3})
+    return rows
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (tokens are independent; "
+              "see DESIGN.md for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2603_08343_amd as wht
+    from paper_2603_08343_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    wht.library()                                         # fail loudly if the HIP library is missing
+    w = synth.WORKLOADS[args.workload]
+
+    bench = Bench(torch, wht, synth, args.workload)
+    step_ms, fwd_ms, bwd_ms = bench.run(args.steps, args.warmup)
+    head = summarize(w, step_ms, fwd_ms, bwd_ms)
+    del bench
+    torch.cuda.empty_cache()
+
+    # roofline of the dominant kernel: backward where the workload has one
+    dom = "bwd" if w.backward else "fwd"
+    dom_ms = bwd_ms if w.backward else fwd_ms
+    dom_bytes = algorithmic_bytes(w.N, w.d, w.dtype, dom)
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "backward_kernel (+ reduce_partials_kernel)" if w.backward else "forward_kernel",
+                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": None, "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms}
+
+    result = {
+        "metric": "wht_affine_fwd_bwd_tokens_per_s" if w.backward else "wht_affine_fwd_tokens_per_s",
+        "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": step_ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={w.N} tokens, d={w.d}, {w.dtype} I/O with f32 arithmetic, "
+                               f"{'forward+backward' if w.backward else 'forward'}",
+                   "buffer_sets_rotated": None},
+        "roofline": roofline,
+        "headline": head,
+    }
+
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(synth, w, args.cpu_seconds)
+    else:
+        result["cpu_baseline"] = None
+
+    if not args.no_extras:
+        extras = {}
+        extras["copy_ceiling"] = copy_ceiling(torch, wht)
+        others = [n for n in ("C4b_roofline", "C5_large", "C2_train", "C3_prefill") if n != args.workload]
+        extras["workloads"] = []
+        for name in others:
+            b = Bench(torch, wht, synth, name)
+            s, f, bw = b.run(max(10, args.steps // 2), 5)
+            extras["workloads"].append(summarize(synth.WORKLOADS[name], s, f, bw))
+            del b
+            torch.cuda.empty_cache()
+        extras["decode"] = decode_latency(torch, wht, synth)
+        extras["dense_wo_same_shape"] = dense_wo(torch, w)
+        extras["dense_wo_same_shape"]["workload"] = w.name
+        result["extras"] = extras
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

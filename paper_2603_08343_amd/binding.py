@@ -131,8 +131,10 @@ def wht_affine_forward(x, alpha, beta, y=None, stream=None):
         y = torch.empty_like(x)
     else:
         _check_io(y, "y", torch, like=x)
+    # torch gives an empty tensor a NULL address; the library never touches x, y when N = 0
+    xp, yp = (x.data_ptr(), y.data_ptr()) if N > 0 else (alpha.data_ptr(), alpha.data_ptr())
     with torch.cuda.device(x.device):
-        rc = wht_affine_forward_raw(x.data_ptr(), alpha.data_ptr(), beta.data_ptr(), y.data_ptr(), N, d,
+        rc = wht_affine_forward_raw(xp, alpha.data_ptr(), beta.data_ptr(), yp, N, d,
                                     _dtype_code(x, torch), _stream_handle(stream, torch, x.device))
     if rc != 0:
         raise WhtAffineError(rc, "wht_affine_forward")
@@ -165,8 +167,9 @@ def wht_affine_backward(dy, x, alpha, dx=None, dalpha=None, dbeta=None, workspac
     elif not workspace.is_cuda or not workspace.is_contiguous() or workspace.device != x.device:
         raise ValueError("workspace must be a contiguous GPU tensor on x's device")
     ws_bytes = workspace.numel() * workspace.element_size()
+    io = (dy.data_ptr(), x.data_ptr(), dx.data_ptr()) if N > 0 else (alpha.data_ptr(),) * 3
     with torch.cuda.device(x.device):
-        rc = wht_affine_backward_raw(dy.data_ptr(), x.data_ptr(), alpha.data_ptr(), dx.data_ptr(),
+        rc = wht_affine_backward_raw(io[0], io[1], alpha.data_ptr(), io[2],
                                      dalpha.data_ptr(), dbeta.data_ptr(), N, d, code,
                                      workspace.data_ptr(), ws_bytes,
                                      _stream_handle(stream, torch, x.device))

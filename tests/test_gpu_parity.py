@@ -262,7 +262,7 @@ def test_boundary_errors_on_gpu():
 
 
 def test_copy_baseline_copies():
-    src = torch.randint(-2 ** 31, 2 ** 31 - 1, (1 << 20) + 4, dtype=torch.int32, device="cuda")
+    src = torch.randint(-2 ** 31, 2 ** 31 - 1, ((1 << 20) + 4,), dtype=torch.int32, device="cuda")
     dst = torch.zeros_like(src)
     wht.wht_affine_copy_baseline(src, dst)
     torch.cuda.synchronize()
