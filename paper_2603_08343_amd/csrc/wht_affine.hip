@@ -6,6 +6,7 @@
 // into the transform's epilogue.  No matrix is stored and no MFMA is used: the work is adds.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <type_traits>
 
 #include "../../include/wht_affine.h"
@@ -25,6 +26,17 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// x, dy are read once and y, dx written once: stream them past the caches (non-temporal).
+__device__ __forceinline__ uint4 stream_load16(const void* p) {
+    const u32x4 v = __builtin_nontemporal_load(static_cast<const u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void stream_store16(void* p, const uint4& q) {
+    const u32x4 v = {q.x, q.y, q.z, q.w};
+    __builtin_nontemporal_store(v, static_cast<u32x4*>(p));
+}
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 // I/O element traits: how one 16-byte global vector maps to float32 registers.
@@ -204,7 +216,7 @@ __device__ __forceinline__ void global_get(float (&r)[C::E], const typename C::i
         constexpr int Cc = decltype(c)::value;
         constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V);
         uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-        if (active) raw = *reinterpret_cast<const uint4*>(row + thread_elem + off);
+        if (active) raw = stream_load16(row + thread_elem + off);
         C::io::unpack(raw, &r[Cc * C::V]);
     });
 }
@@ -215,7 +227,7 @@ __device__ __forceinline__ void global_put(const float (&r)[C::E], typename C::i
     static_for<0, C::NV>([&](auto c) {
         constexpr int Cc = decltype(c)::value;
         constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V);
-        if (active) *reinterpret_cast<uint4*>(row + thread_elem + off) = C::io::pack(&r[Cc * C::V]);
+        if (active) stream_store16(row + thread_elem + off, C::io::pack(&r[Cc * C::V]));
     });
 }
 
@@ -340,25 +352,33 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
     }
 }
 
-// out[which][j] = sum over rows of partials[row][which][j], rows added in index order.
-// Workgroup = 64 columns x 4 row lanes; the 4 lane sums are added in lane order.
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partials,
-                                                              int rows, int d,
-                                                              float* __restrict__ dalpha,
-                                                              float* __restrict__ dbeta) {
-    __shared__ float part[4][64];
-    const int col = blockIdx.x * 64 + (threadIdx.x & 63);
-    const int lane_row = threadIdx.x >> 6;
+// out[which][j] = sum over rows of partials[row][which][j].  Workgroup = 16 float4 columns x 64
+// row lanes: lane r adds rows r, r+64, ... in index order, then the 64 lane sums are added in lane
+// order -- a fixed association, independent of scheduling.
+__global__ __launch_bounds__(1024) void reduce_partials_kernel(const float* __restrict__ partials,
+                                                               int rows, int d,
+                                                               float* __restrict__ dalpha,
+                                                               float* __restrict__ dbeta) {
+    __shared__ float4 part[64][16];
+    const int cg = threadIdx.x & 15, lane_row = threadIdx.x >> 4;
+    const int col = (blockIdx.x * 16 + cg) * 4;           // first of this thread's 4 columns
     const int which = blockIdx.y;
-    float acc = 0.0f;
-    if (col < d)
-        for (int r = lane_row; r < rows; r += 4) acc += partials[((size_t)r * 2 + which) * d + col];
-    part[lane_row][threadIdx.x & 63] = acc;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (col < d) {
+        for (int r = lane_row; r < rows; r += 64) {
+            const float4 q = *reinterpret_cast<const float4*>(partials + ((size_t)r * 2 + which) * d + col);
+            acc.x += q.x; acc.y += q.y; acc.z += q.z; acc.w += q.w;
+        }
+    }
+    part[lane_row][cg] = acc;
     __syncthreads();
     if (lane_row == 0 && col < d) {
-        const int c = threadIdx.x & 63;
-        const float total = ((part[0][c] + part[1][c]) + part[2][c]) + part[3][c];
-        (which == 0 ? dalpha : dbeta)[col] = total;
+        float4 t = part[0][cg];
+        for (int r = 1; r < 64; ++r) {
+            const float4 q = part[r][cg];
+            t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+        }
+        *reinterpret_cast<float4*>((which == 0 ? dalpha : dbeta) + col) = t;
     }
 }
 
@@ -385,12 +405,25 @@ __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src
 // host side: launch shapes and dispatch
 
 constexpr int kNumCU = 256;             // MI355X
-constexpr int kMaxGroupsPerCU = 4;      // resident workgroups per CU the grid is sized for
+
+// Workgroups launched per CU (the grid is persistent: each workgroup strides over token groups).
+// The defaults are the measured optima; the environment variables exist for tuning runs only.
+static int env_int(const char* name, int fallback) {
+    const char* v = getenv(name);
+    if (!v || !*v) return fallback;
+    const int x = atoi(v);
+    return (x >= 1 && x <= 64) ? x : fallback;
+}
+static int groups_per_cu(bool backward) {
+    static const int fwd = env_int("WHT_AFFINE_FWD_GROUPS_PER_CU", 4);
+    static const int bwd = env_int("WHT_AFFINE_BWD_GROUPS_PER_CU", 2);
+    return backward ? bwd : fwd;
+}
 
 template <class C>
-static int grid_for(int64_t N) {
+static int grid_for(int64_t N, bool backward) {
     const int64_t groups = (N + C::G - 1) / C::G;
-    const int64_t cap = (int64_t)kNumCU * kMaxGroupsPerCU;
+    const int64_t cap = (int64_t)kNumCU * groups_per_cu(backward);
     return (int)(groups < cap ? groups : cap);
 }
 
@@ -410,7 +443,7 @@ static int launch_forward(const void* x, const float* alpha, const float* beta, 
                           hipStream_t stream) {
     using T = typename C::io::elem_t;
     if (!allow_lds<C>(forward_kernel<C>)) return WHT_ERR_LAUNCH;
-    hipLaunchKernelGGL(forward_kernel<C>, dim3(grid_for<C>(N)), dim3(C::BT), C::kLdsBytes, stream,
+    hipLaunchKernelGGL(forward_kernel<C>, dim3(grid_for<C>(N, false)), dim3(C::BT), C::kLdsBytes, stream,
                        static_cast<const T*>(x), alpha, beta, static_cast<T*>(y), N);
     return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
 }
@@ -419,19 +452,19 @@ template <class C>
 static int launch_backward(const void* dy, const void* x, const float* alpha, void* dx, float* dalpha,
                            float* dbeta, int64_t N, void* workspace, hipStream_t stream) {
     using T = typename C::io::elem_t;
-    const int grid = grid_for<C>(N);
+    const int grid = grid_for<C>(N, true);
     if (!allow_lds<C>(backward_kernel<C>)) return WHT_ERR_LAUNCH;
     hipLaunchKernelGGL(backward_kernel<C>, dim3(grid), dim3(C::BT), C::kLdsBytes, stream,
                        static_cast<const T*>(dy), static_cast<const T*>(x), alpha, static_cast<T*>(dx),
                        static_cast<float*>(workspace), N);
     if (hipGetLastError() != hipSuccess) return WHT_ERR_LAUNCH;
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((C::D + 63) / 64, 2), dim3(256), 0, stream,
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((C::D + 63) / 64, 2), dim3(1024), 0, stream,
                        static_cast<const float*>(workspace), grid, C::D, dalpha, dbeta);
     return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
 }
 
 template <class C>
-static size_t workspace_for(int64_t N) { return (size_t)grid_for<C>(N) * 2 * C::D * sizeof(float); }
+static size_t workspace_for(int64_t N) { return (size_t)grid_for<C>(N, true) * 2 * C::D * sizeof(float); }
 
 enum class Op { Forward, Backward, Workspace };
 
