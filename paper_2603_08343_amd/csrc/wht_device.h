@@ -1,0 +1,577 @@
+// Device code of the Walsh-Hadamard output layer  y = alpha (.) (H x) + beta  (paper Sec. 4.1,
+// Eq. 1) for gfx950: the per-token transform H_raw x (Fig. 2's butterfly stages, scheduled by
+// wht_plan.h), the fused affine epilogue, the backward pass with z recomputed, and the fixed-order
+// reduction of dalpha / dbeta.  1/sqrt(d) is folded into alpha.  Two schedules share the kernels:
+//   - butterfly schedule (float32 I/O, and bfloat16 below d = 1024): every stage is adds/subtracts
+//     on register pairs; the token is re-dealt through LDS between groups of stages;
+//   - matrix-core schedule (bfloat16 I/O, d >= 1024): ten of the log2(d) stages run as two rounds
+//     of 32x32 +-1 products on the MFMA unit (exact products, float32 accumulation), the rest as
+//     register butterflies plus one LDS exchange across the waves of a token.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <type_traits>
+
+#include "wht_plan.h"
+
+namespace wht {
+
+// ------------------------------------------------------------------------------------------------
+// small helpers
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// x, dy are read once and y, dx written once: stream them past the caches (non-temporal).
+__device__ __forceinline__ uint4 stream_load16(const void* p) {
+    const u32x4 v = __builtin_nontemporal_load(static_cast<const u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void stream_store16(void* p, const uint4& q) {
+    const u32x4 v = {q.x, q.y, q.z, q.w};
+    __builtin_nontemporal_store(v, static_cast<u32x4*>(p));
+}
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// I/O element traits: how one 16-byte global vector maps to float32 registers.
+struct IoF32 {
+    using elem_t = float;
+    static constexpr int kLogVec = 2;   // 4 elements per 16 bytes
+    static __device__ __forceinline__ void unpack(const uint4& raw, float* out) {
+        out[0] = __uint_as_float(raw.x); out[1] = __uint_as_float(raw.y);
+        out[2] = __uint_as_float(raw.z); out[3] = __uint_as_float(raw.w);
+    }
+    static __device__ __forceinline__ uint4 pack(const float* in) {
+        return make_uint4(__float_as_uint(in[0]), __float_as_uint(in[1]),
+                          __float_as_uint(in[2]), __float_as_uint(in[3]));
+    }
+};
+
+struct IoBF16 {
+    using elem_t = uint16_t;
+    static constexpr int kLogVec = 3;   // 8 elements per 16 bytes
+    // bfloat16 is the upper half of binary32: widening is a shift / a mask
+    static __device__ __forceinline__ void unpack(const uint4& raw, float* out) {
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i]     = __uint_as_float(w[i] << 16);
+            out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    // round to nearest even (the hardware's packed float32 -> bfloat16 convert)
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+        f32x2 f = {lo, hi};
+        bf16x2 b = __builtin_convertvector(f, bf16x2);
+        return __builtin_bit_cast(uint32_t, b);
+    }
+    static __device__ __forceinline__ uint4 pack(const float* in) {
+        return make_uint4(pack2(in[0], in[1]), pack2(in[2], in[3]),
+                          pack2(in[4], in[5]), pack2(in[6], in[7]));
+    }
+};
+
+// ------------------------------------------------------------------------------------------------
+// per-(d, dtype) configuration
+
+// Butterfly schedule.
+template <int LOGD, int LOGE, class Io>
+struct Cfg {
+    using io = Io;
+    static constexpr bool kMfma = false;
+    static constexpr int n = LOGD, e = LOGE, v = Io::kLogVec;
+    static_assert(v <= e && e <= n && e <= kMaxRegBits, "bad tile");
+    static constexpr PlanDesc plan = make_plan(n, e, v);
+    static_assert(plan_is_complete(plan), "every butterfly stage must run exactly once");
+    static constexpr int P = plan.nphase;
+    static constexpr int D = 1 << n;
+    static constexpr int E = 1 << e;            // values per thread
+    static constexpr int V = 1 << v;            // elements per 16-byte vector
+    static constexpr int NV = E / V;            // 16-byte vectors per thread
+    static constexpr int TPT = 1 << (n - e);    // threads per token
+    static constexpr int BT = TPT > 256 ? TPT : 256;   // threads per workgroup
+    static constexpr int G = BT / TPT;          // tokens per workgroup pass
+    static constexpr unsigned phys(unsigned i) { return lds_phys(i); }
+    static constexpr unsigned kTokenWords = lds_words_skew(D);
+    static constexpr unsigned kLdsBytes = (P > 1 || G > 1) ? G * kTokenWords * 4u : 16u;
+    static_assert(kLdsBytes <= 160u * 1024u, "token group does not fit LDS");
+};
+
+// Matrix-core schedule (bfloat16 I/O, d >= 1024): 2^LOGT MFMA tiles of 1024 elements per wave.
+template <int LOGD, int LOGT>
+struct MfmaCfg {
+    using io = IoBF16;
+    static constexpr bool kMfma = true;
+    static constexpr int n = LOGD, t = LOGT, e = 4 + LOGT, v = 3;
+    static constexpr int w = n - 10 - t;        // log2(waves per token)
+    static_assert(n >= 10 && w >= 0 && w <= 1 + t && e <= kMaxRegBits, "bad tile");
+    static constexpr PlanDesc plan = make_mfma_plan(n, t);
+    static_assert(plan_is_complete(plan), "every stage must run exactly once");
+    static constexpr int P = plan.nphase;
+    static constexpr int D = 1 << n;
+    static constexpr int E = 1 << e;
+    static constexpr int V = 8;
+    static constexpr int NV = E / V;
+    static constexpr int T = 1 << t;            // MFMA tiles per wave
+    static constexpr int TPT = 1 << (n - e);
+    static_assert(TPT >= 64, "a token occupies whole waves");
+    static constexpr int BT = TPT > 256 ? TPT : 256;
+    static constexpr int G = BT / TPT;
+    static constexpr unsigned phys(unsigned i) { return lds_phys_rot(i); }
+    static constexpr unsigned kTokenWords = D;
+    static constexpr unsigned kLdsBytes = (P > 1 || G > 1) ? G * kTokenWords * 4u : 16u;
+    static_assert(kLdsBytes <= 160u * 1024u, "token group does not fit LDS");
+};
+
+// Element offset of thread t (within its token) in phase PH.
+template <class C, int PH>
+__device__ __forceinline__ unsigned thread_elem_offset(unsigned t) {
+    unsigned off = 0;
+    static_for<0, C::n - C::e>([&](auto k) {
+        constexpr int K = decltype(k)::value;
+        off |= ((t >> K) & 1u) << C::plan.ph[PH].tb[K];
+    });
+    return off;
+}
+
+// Butterfly stages of phase PH, all in registers: (a, b) -> (a + b, a - b) on register pairs.
+template <class C, int PH>
+__device__ __forceinline__ void run_stages(float (&r)[C::E]) {
+    static_for<0, C::e>([&](auto q) {
+        constexpr int Q = decltype(q)::value;
+        constexpr int bit = C::plan.ph[PH].rb[Q];
+        if constexpr ((C::plan.ph[PH].stages >> bit) & 1u) {
+            static_for<0, C::E>([&](auto i) {
+                constexpr int I = decltype(i)::value;
+                if constexpr (!((I >> Q) & 1)) {
+                    const float a = r[I], b = r[I | (1 << Q)];
+                    r[I] = a + b;
+                    r[I | (1 << Q)] = a - b;
+                }
+            });
+        }
+    });
+}
+
+template <class C, int PH>
+constexpr bool phase_is_vec4() { return C::plan.ph[PH].rb[0] == 0 && C::plan.ph[PH].rb[1] == 1; }
+
+// Registers <-> LDS in the layout of phase PH.  `tok` points at this token's LDS region plus the
+// thread's own (runtime) offset; register offsets are compile-time immediates.
+template <class C, int PH>
+__device__ __forceinline__ void lds_put(const float (&r)[C::E], float* tok) {
+    if constexpr (phase_is_vec4<C, PH>()) {
+        static_for<0, C::E / 4>([&](auto i) {
+            constexpr int I = decltype(i)::value * 4;
+            constexpr unsigned off = C::phys(reg_elem_offset(C::plan.ph[PH], C::e, I));
+            *reinterpret_cast<float4*>(tok + off) = make_float4(r[I], r[I + 1], r[I + 2], r[I + 3]);
+        });
+    } else {
+        static_for<0, C::E>([&](auto i) {
+            constexpr int I = decltype(i)::value;
+            constexpr unsigned off = C::phys(reg_elem_offset(C::plan.ph[PH], C::e, I));
+            tok[off] = r[I];
+        });
+    }
+}
+
+template <class C, int PH>
+__device__ __forceinline__ void lds_get(float (&r)[C::E], const float* tok) {
+    if constexpr (phase_is_vec4<C, PH>()) {
+        static_for<0, C::E / 4>([&](auto i) {
+            constexpr int I = decltype(i)::value * 4;
+            constexpr unsigned off = C::phys(reg_elem_offset(C::plan.ph[PH], C::e, I));
+            const float4 q = *reinterpret_cast<const float4*>(tok + off);
+            r[I] = q.x; r[I + 1] = q.y; r[I + 2] = q.z; r[I + 3] = q.w;
+        });
+    } else {
+        static_for<0, C::E>([&](auto i) {
+            constexpr int I = decltype(i)::value;
+            constexpr unsigned off = C::phys(reg_elem_offset(C::plan.ph[PH], C::e, I));
+            r[I] = tok[off];
+        });
+    }
+}
+
+// Per-thread constants: LDS word offset of the thread in every phase, element offset in the first
+// and last phase (the global-memory layouts).
+template <class C>
+struct ThreadMap {
+    unsigned lds_off[kMaxPhases];
+    unsigned first_elem, last_elem;
+    __device__ __forceinline__ void init(unsigned t, unsigned slot) {
+        static_for<0, C::P>([&](auto p) {
+            constexpr int PH = decltype(p)::value;
+            lds_off[PH] = slot * C::kTokenWords + C::phys(thread_elem_offset<C, PH>(t));
+        });
+        first_elem = thread_elem_offset<C, 0>(t);
+        last_elem = thread_elem_offset<C, C::P - 1>(t);
+    }
+};
+
+// H_raw applied to the 2^n values spread over the token's threads.
+//   FORWARD_ORDER: registers enter in the first phase's layout and leave in the last phase's;
+//   otherwise the phases run in reverse (enter in the last layout, leave in the first) -- the
+//   backward pass uses this so that dy can be consumed in the layout z was produced in.
+// Ends with a workgroup barrier when LDS was used, so the caller may reuse LDS at once.
+template <class C, bool FORWARD_ORDER>
+__device__ __forceinline__ void transform(float (&r)[C::E], float* lds, const ThreadMap<C>& tm) {
+    static_for<0, C::P>([&](auto s) {
+        constexpr int S = decltype(s)::value;
+        constexpr int PH = FORWARD_ORDER ? S : C::P - 1 - S;
+        if constexpr (S > 0) lds_get<C, PH>(r, lds + tm.lds_off[PH]);
+        run_stages<C, PH>(r);
+        if constexpr (S + 1 < C::P) {
+            // a middle phase rewrites exactly the words it read, so only the hand-over to the
+            // next layout needs the barrier
+            lds_put<C, PH>(r, lds + tm.lds_off[PH]);
+            __syncthreads();
+        }
+    });
+    if constexpr (C::P > 1) __syncthreads();
+}
+
+// Global <-> registers in the layout of phase PH (first or last): 16 bytes per lane per access.
+template <class C, int PH>
+__device__ __forceinline__ void global_get(float (&r)[C::E], const typename C::io::elem_t* row,
+                                           unsigned thread_elem, bool active) {
+    static_for<0, C::NV>([&](auto c) {
+        constexpr int Cc = decltype(c)::value;
+        constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V);
+        uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+        if (active) raw = stream_load16(row + thread_elem + off);
+        C::io::unpack(raw, &r[Cc * C::V]);
+    });
+}
+
+template <class C, int PH>
+__device__ __forceinline__ void global_put(const float (&r)[C::E], typename C::io::elem_t* row,
+                                           unsigned thread_elem, bool active) {
+    static_for<0, C::NV>([&](auto c) {
+        constexpr int Cc = decltype(c)::value;
+        constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V);
+        if (active) stream_store16(row + thread_elem + off, C::io::pack(&r[Cc * C::V]));
+    });
+}
+
+// float32 parameter vector -> registers in the layout of phase PH, times `scale`.
+template <class C, int PH>
+__device__ __forceinline__ void param_get(float (&r)[C::E], const float* p, unsigned thread_elem,
+                                          float scale) {
+    static_for<0, C::E / 4>([&](auto i) {
+        constexpr int I = decltype(i)::value * 4;
+        constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, I);
+        const float4 q = *reinterpret_cast<const float4*>(p + thread_elem + off);
+        r[I] = q.x * scale; r[I + 1] = q.y * scale; r[I + 2] = q.z * scale; r[I + 3] = q.w * scale;
+    });
+}
+
+// 16-byte global vectors as loaded, no widening (they are MFMA A operands as they stand).
+template <class C, int PH>
+__device__ __forceinline__ void global_get_raw(uint4 (&raw)[C::NV], const typename C::io::elem_t* row,
+                                               unsigned thread_elem, bool active) {
+    static_for<0, C::NV>([&](auto c) {
+        constexpr int Cc = decltype(c)::value;
+        constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V);
+        raw[Cc] = make_uint4(0u, 0u, 0u, 0u);
+        if (active) raw[Cc] = stream_load16(row + thread_elem + off);
+    });
+}
+
+// ------------------------------------------------------------------------------------------------
+// matrix-core rounds: H_32 along five element bits as a 32x32x32 product with a +-1 matrix
+//
+// v_mfma_f32_32x32x16_bf16 operand layout (two instructions cover K = 32):
+//   A[i][k]: lane = i + 32*(k/8 % 2), element k%8 of the lane's 8 bf16, instruction k/16
+//   B[k][j]: lane = j + 32*(k/8 % 2), element k%8, instruction k/16
+//   D[i][j]: lane = j + 32*(i/4 % 2), register 4*(i/8) + i%4
+// With B[k][j] = (-1)^popcount(k & swap23(j)) (bits 2 and 3 of j exchanged) the accumulator of a
+// round is again an A operand for the next one -- rows <-> the previous round's outputs, K <-> the
+// previous round's rows -- and after two rounds each lane holds, in register order, the 8 + 8
+// consecutive elements it loaded.
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct HadamardB {
+    bf16x8 k_lo, k_hi;      // B operand of the first / second K-half
+};
+
+__device__ __forceinline__ HadamardB make_hadamard_b() {
+    const unsigned lane = threadIdx.x & 63u;
+    const unsigned j = lane & 31u, kg = lane >> 5;
+    const unsigned js = (j & 0x13u) | ((j & 4u) << 1) | ((j & 8u) >> 1);
+    uint32_t w[2][4];
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const unsigned k0 = (2u * p) | (kg << 3) | ((unsigned)half << 4), k1 = k0 | 1u;
+            const uint32_t lo = (__popc(k0 & js) & 1) ? 0xBF80u : 0x3F80u;     // bf16 -1 : +1
+            const uint32_t hi = (__popc(k1 & js) & 1) ? 0xBF80u : 0x3F80u;
+            w[half][p] = lo | (hi << 16);
+        }
+    HadamardB b;
+    b.k_lo = __builtin_bit_cast(bf16x8, make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]));
+    b.k_hi = __builtin_bit_cast(bf16x8, make_uint4(w[1][0], w[1][1], w[1][2], w[1][3]));
+    return b;
+}
+
+// One round on bfloat16 data straight from memory: products and sums are exact up to the
+// accumulator's float32 rounding.
+__device__ __forceinline__ f32x16 hadamard_round_bf16(const uint4& a_lo, const uint4& a_hi,
+                                                      const HadamardB& b) {
+    f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_lo), b.k_lo, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a_hi), b.k_hi, acc, 0, 0, 0);
+    return acc;
+}
+
+// One round on float32 data: each value is split into bf16 hi + bf16 lo (hi = RNE(v), lo =
+// RNE(v - hi); v - hi is exact, so |v - hi - lo| <= 2^-18 |v|) and both parts go through the same
+// +-1 product, accumulated in float32.
+__device__ __forceinline__ f32x16 hadamard_round_f32(const float* v, const HadamardB& b) {
+    uint32_t hi[8], lo[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        const uint32_t h = IoBF16::pack2(v[2 * p], v[2 * p + 1]);
+        const float h0 = __uint_as_float(h << 16), h1 = __uint_as_float(h & 0xffff0000u);
+        hi[p] = h;
+        lo[p] = IoBF16::pack2(v[2 * p] - h0, v[2 * p + 1] - h1);
+    }
+    f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const bf16x8 lo0 = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+    const bf16x8 lo1 = __builtin_bit_cast(bf16x8, make_uint4(lo[4], lo[5], lo[6], lo[7]));
+    const bf16x8 hi0 = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+    const bf16x8 hi1 = __builtin_bit_cast(bf16x8, make_uint4(hi[4], hi[5], hi[6], hi[7]));
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo0, b.k_lo, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo1, b.k_hi, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi0, b.k_lo, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi1, b.k_hi, acc, 0, 0, 0);
+    return acc;
+}
+
+// Both rounds on every tile of the thread: bits 0..9 of the element index.
+//   from raw bfloat16 (the forward input x): round 1 needs no split
+template <class C>
+__device__ __forceinline__ void mfma_rounds_from_bf16(float (&r)[C::E], const uint4 (&raw)[C::NV],
+                                                      const HadamardB& b) {
+    static_for<0, C::T>([&](auto tile) {
+        constexpr int Tl = decltype(tile)::value;
+        const f32x16 d1 = hadamard_round_bf16(raw[2 * Tl], raw[2 * Tl + 1], b);
+        float v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = d1[i];
+        const f32x16 d2 = hadamard_round_f32(v, b);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) r[16 * Tl + i] = d2[i];
+    });
+}
+//   from float32 registers in the first layout (the backward pass's alpha' (.) dy)
+template <class C>
+__device__ __forceinline__ void mfma_rounds_from_f32(float (&r)[C::E], const HadamardB& b) {
+    static_for<0, C::T>([&](auto tile) {
+        constexpr int Tl = decltype(tile)::value;
+        const f32x16 d1 = hadamard_round_f32(&r[16 * Tl], b);
+        float v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = d1[i];
+        const f32x16 d2 = hadamard_round_f32(v, b);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) r[16 * Tl + i] = d2[i];
+    });
+}
+
+// x[tok] -> H_raw x in the last layout, whichever schedule C is.
+template <class C>
+__device__ __forceinline__ void load_and_transform(float (&r)[C::E], const typename C::io::elem_t* row,
+                                                   float* lds, const ThreadMap<C>& tm,
+                                                   const HadamardB& b, bool active) {
+    if constexpr (C::kMfma) {
+        uint4 raw[C::NV];
+        global_get_raw<C, 0>(raw, row, tm.first_elem, active);
+        mfma_rounds_from_bf16<C>(r, raw, b);
+    } else {
+        global_get<C, 0>(r, row, tm.first_elem, active);
+    }
+    transform<C, true>(r, lds, tm);
+}
+
+// registers in the last layout -> H_raw (.) in the first layout.
+template <class C>
+__device__ __forceinline__ void transform_back(float (&r)[C::E], float* lds, const ThreadMap<C>& tm,
+                                               const HadamardB& b) {
+    transform<C, false>(r, lds, tm);
+    if constexpr (C::kMfma) mfma_rounds_from_f32<C>(r, b);
+}
+
+template <class C>
+__device__ __forceinline__ float inv_sqrt_d() {
+    // exact power of two for even log2 d; one rounding of 1/sqrt(2) * 2^-k otherwise
+    return (C::n % 2 == 0) ? 1.0f / float(1 << (C::n / 2))
+                           : 0.70710678118654752440f / float(1 << (C::n / 2));
+}
+
+// ------------------------------------------------------------------------------------------------
+// forward:  y = (alpha / sqrt d) (.) (H_raw x) + beta
+
+template <class C>
+__global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::elem_t* x,
+                                                        const float* __restrict__ alpha,
+                                                        const float* __restrict__ beta,
+                                                        typename C::io::elem_t* y,
+                                                        int64_t N) {
+    extern __shared__ __align__(16) float lds[];
+    constexpr int LAST = C::P - 1;
+    const unsigned t = threadIdx.x % C::TPT, slot = threadIdx.x / C::TPT;
+    ThreadMap<C> tm;
+    tm.init(t, slot);
+    HadamardB hb{};
+    if constexpr (C::kMfma) hb = make_hadamard_b();
+
+    float a[C::E], b[C::E];
+    param_get<C, LAST>(a, alpha, tm.last_elem, inv_sqrt_d<C>());
+    param_get<C, LAST>(b, beta, tm.last_elem, 1.0f);
+
+    const int64_t groups = (N + C::G - 1) / C::G;
+    for (int64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+        const int64_t tok = grp * C::G + slot;
+        const bool active = tok < N;
+        float r[C::E];
+        load_and_transform<C>(r, x + tok * C::D, lds, tm, hb, active);
+#pragma unroll
+        for (int i = 0; i < C::E; ++i) r[i] = fmaf(r[i], a[i], b[i]);
+        global_put<C, LAST>(r, y + tok * C::D, tm.last_elem, active);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward:  z = H x (recomputed);  dalpha += dy z;  dbeta += dy;  dx = H_raw((alpha/sqrt d) dy)
+// Each workgroup walks a strided set of token groups, keeps its dalpha/dbeta sums in registers,
+// and at the end writes one row of partial sums; reduce_partials_kernel adds the rows in a fixed
+// order, so the result does not depend on scheduling.
+
+template <class C>
+__global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::elem_t* dy,
+                                                         const typename C::io::elem_t* x,
+                                                         const float* __restrict__ alpha,
+                                                         typename C::io::elem_t* dx,
+                                                         float* __restrict__ partials,   // [grid][2][D]
+                                                         int64_t N) {
+    extern __shared__ __align__(16) float lds[];
+    constexpr int LAST = C::P - 1;
+    const unsigned t = threadIdx.x % C::TPT, slot = threadIdx.x / C::TPT;
+    ThreadMap<C> tm;
+    tm.init(t, slot);
+    HadamardB hb{};
+    if constexpr (C::kMfma) hb = make_hadamard_b();
+
+    float a[C::E], da[C::E], db[C::E];
+    param_get<C, LAST>(a, alpha, tm.last_elem, inv_sqrt_d<C>());
+#pragma unroll
+    for (int i = 0; i < C::E; ++i) { da[i] = 0.0f; db[i] = 0.0f; }
+
+    const int64_t groups = (N + C::G - 1) / C::G;
+    for (int64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+        const int64_t tok = grp * C::G + slot;
+        const bool active = tok < N;
+        float r[C::E], g[C::E];
+        load_and_transform<C>(r, x + tok * C::D, lds, tm, hb, active);   // r = H_raw x, last layout
+        global_get<C, LAST>(g, dy + tok * C::D, tm.last_elem, active);
+#pragma unroll
+        for (int i = 0; i < C::E; ++i) {
+            da[i] = fmaf(g[i], r[i], da[i]);                  // 1/sqrt d applied once at the end
+            db[i] += g[i];
+            g[i] *= a[i];
+        }
+        transform_back<C>(g, lds, tm, hb);                    // g = H_raw(alpha' dy), first layout
+        global_put<C, 0>(g, dx + tok * C::D, tm.first_elem, active);
+    }
+
+    // Sum the G token slots of this workgroup through LDS, then write the workgroup's row.
+    const float s = inv_sqrt_d<C>();
+    float* row = partials + (size_t)blockIdx.x * 2 * C::D;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+        if constexpr (C::G == 1) {
+            static_for<0, C::E / 4>([&](auto i) {
+                constexpr int I = decltype(i)::value * 4;
+                constexpr unsigned off = reg_elem_offset(C::plan.ph[LAST], C::e, I);
+                const float4 q = which == 0 ? make_float4(da[I] * s, da[I + 1] * s, da[I + 2] * s, da[I + 3] * s)
+                                            : make_float4(db[I], db[I + 1], db[I + 2], db[I + 3]);
+                *reinterpret_cast<float4*>(row + which * C::D + tm.last_elem + off) = q;
+            });
+        } else {
+            if (which == 0) lds_put<C, LAST>(da, lds + tm.lds_off[LAST]);
+            else            lds_put<C, LAST>(db, lds + tm.lds_off[LAST]);
+            __syncthreads();
+            for (unsigned j = threadIdx.x; j < (unsigned)C::D; j += C::BT) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int gslot = 0; gslot < C::G; ++gslot) acc += lds[gslot * C::kTokenWords + C::phys(j)];
+                row[which * C::D + j] = which == 0 ? acc * s : acc;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// out[which][j] = sum over rows of partials[row][which][j].  Workgroup = 16 float4 columns x 64
+// row lanes: lane r adds rows r, r+64, ... in index order, then the 64 lane sums are added in lane
+// order -- a fixed association, independent of scheduling.
+__global__ __launch_bounds__(1024) void reduce_partials_kernel(const float* __restrict__ partials,
+                                                               int rows, int d,
+                                                               float* __restrict__ dalpha,
+                                                               float* __restrict__ dbeta) {
+    __shared__ float4 part[64][16];
+    const int cg = threadIdx.x & 15, lane_row = threadIdx.x >> 4;
+    const int col = (blockIdx.x * 16 + cg) * 4;           // first of this thread's 4 columns
+    const int which = blockIdx.y;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (col < d) {
+        for (int r = lane_row; r < rows; r += 64) {
+            const float4 q = *reinterpret_cast<const float4*>(partials + ((size_t)r * 2 + which) * d + col);
+            acc.x += q.x; acc.y += q.y; acc.z += q.z; acc.w += q.w;
+        }
+    }
+    part[lane_row][cg] = acc;
+    __syncthreads();
+    if (lane_row == 0 && col < d) {
+        float4 t = part[0][cg];
+        for (int r = 1; r < 64; ++r) {
+            const float4 q = part[r][cg];
+            t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+        }
+        *reinterpret_cast<float4*>((which == 0 ? dalpha : dbeta) + col) = t;
+    }
+}
+
+__global__ void zero_kernel(float* a, float* b, int d) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < d) { a[i] = 0.0f; b[i] = 0.0f; }
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                   size_t nvec) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x * 4;
+    for (size_t base = ((size_t)blockIdx.x * blockDim.x) * 4 + threadIdx.x; base < nvec; base += stride) {
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (base + k * 256 < nvec) v[k] = src[base + k * 256];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (base + k * 256 < nvec) dst[base + k * 256] = v[k];
+    }
+}
+
+
+}  // namespace wht

@@ -26,6 +26,7 @@ struct PhaseDesc {
 
 struct PlanDesc {
     int n, e, v, nphase;
+    unsigned mfma_bits;    // element bits transformed by the matrix-core rounds (in the first layout)
     PhaseDesc ph[kMaxPhases];
 };
 
@@ -58,7 +59,7 @@ constexpr int log_e_for(int logd, int logv) {
 // n = log2 d, e = log2(values per thread), v = log2(elements per 16-byte vector);  v <= e <= n.
 constexpr PlanDesc make_plan(int n, int e, int v) {
     PlanDesc pl{};
-    pl.n = n; pl.e = e; pl.v = v; pl.nphase = 0;
+    pl.n = n; pl.e = e; pl.v = v; pl.nphase = 0; pl.mfma_bits = 0;
     const unsigned all = (1u << n) - 1u;
     unsigned undone = all;
 
@@ -125,7 +126,7 @@ constexpr unsigned reg_elem_offset(const PhaseDesc& p, int e, int r) {
 
 // Every element bit must be butterflied exactly once over the phases.
 constexpr bool plan_is_complete(const PlanDesc& pl) {
-    unsigned seen = 0;
+    unsigned seen = pl.mfma_bits;
     for (int p = 0; p < pl.nphase; ++p) {
         if (seen & pl.ph[p].stages) return false;
         if (pl.ph[p].stages & ~reg_mask(pl.ph[p], pl.e)) return false;
@@ -134,11 +135,64 @@ constexpr bool plan_is_complete(const PlanDesc& pl) {
     return seen == (1u << pl.n) - 1u;
 }
 
-// LDS word address of element i of a token.  Two skews, both multiples of 4 words so that four
-// consecutive elements stay one aligned 16-byte access: +4 words every 64 elements keeps the
-// 16-byte-per-lane accesses of the first/last layouts off each other's banks, +8 words every 256
-// elements does the same for the one-word accesses of the middle layouts (lanes 256 elements apart).
-// Linear in the bits of i, so phys(a | b) = phys(a) + phys(b) for disjoint a, b.
+// ---- the matrix-core schedule (bfloat16 I/O, d >= 1024) ---------------------------------------
+//
+// H_32 applied along five element bits is a 32x32 (+-1) matrix product, which the MFMA unit does
+// with exact products and float32 accumulation.  Two such rounds cover bits 0..9:
+//   round 1 contracts bits {0,1,2,8,9}: each lane feeds 8 consecutive elements (one 16-byte global
+//           vector, bits 0..2), the lane's upper half selects bit 8, the two instructions bit 9;
+//           the 32 rows are bits 3..7 (lanes 0..31 read 512 contiguous bytes);
+//   round 2 contracts bits {3..7}: the accumulator layout of round 1 has those bits in the register
+//           index and the lane's upper half, which is exactly an A-operand layout again.
+// After round 2 every lane holds 8 consecutive elements per 16 registers -- the layout it loaded
+// in -- so the rounds map the first layout onto itself and leave d/1024 = 2^(t+w) sub-transforms to
+// combine: t "tile" bits in registers (2^t MFMA tiles per wave), w bits across the waves of the
+// token through one LDS exchange into a second layout that holds them in registers.
+//   first layout : registers (0,1,2, 9, 10..10+t-1), lanes (3..8), waves (10+t..n-1)
+//   second layout: registers (0,1,2, the 1+t-w highest of the first layout's upper register bits,
+//                  n-w..n-1), lanes (3..8), waves (the w replaced bits)
+constexpr PlanDesc make_mfma_plan(int n, int t) {
+    PlanDesc pl{};
+    const int e = 4 + t, v = 3, w = n - 10 - t;
+    pl.n = n; pl.e = e; pl.v = v; pl.nphase = 0;
+    pl.mfma_bits = (1u << 10) - 1u;
+    PhaseDesc first{};
+    first.rb[0] = 0; first.rb[1] = 1; first.rb[2] = 2; first.rb[3] = 9;
+    for (int k = 0; k < t; ++k) first.rb[4 + k] = 10 + k;
+    first.stages = 0;
+    for (int k = 0; k < t; ++k) first.stages |= 1u << (10 + k);
+    fill_thread_bits(first, n, e);
+    pl.ph[pl.nphase++] = first;
+    if (w <= 0) return pl;
+    PhaseDesc second{};
+    second.rb[0] = 0; second.rb[1] = 1; second.rb[2] = 2;
+    int q = 3;
+    for (int k = w; k < 1 + t; ++k) second.rb[q++] = first.rb[3 + k];   // kept upper register bits
+    second.stages = 0;
+    for (int k = 0; k < w; ++k) { second.rb[q++] = n - w + k; second.stages |= 1u << (n - w + k); }
+    fill_thread_bits(second, n, e);
+    pl.ph[pl.nphase++] = second;
+    return pl;
+}
+
+// tiles per wave (log2) used for a given log2 d
+constexpr int mfma_log_tiles(int logd) { return logd <= 10 ? 0 : (logd <= 13 ? 1 : 2); }
+
+// ---- LDS address maps -------------------------------------------------------------------------
+// Both are linear in the bits of i (phys(a | b) = phys(a) + phys(b) for disjoint a, b) and keep four
+// consecutive elements in one aligned 16-byte group.
+
+// Butterfly schedule: +4 words every 64 elements keeps the 16-byte-per-lane accesses of the
+// first/last layouts off each other's banks, +8 words every 256 elements does the same for the
+// one-word accesses of the middle layouts (lanes 256 elements apart).
 constexpr unsigned lds_phys(unsigned i) { return i + ((i >> 6) << 2) + ((i >> 8) << 3); }
+constexpr unsigned lds_words_skew(unsigned d) { return (lds_phys(d - 1) + 1 + 3) & ~3u; }
+
+// Matrix-core schedule: both layouts give lane l the 8 elements starting at 8*l (+ multiples of
+// 512) as two 16-byte accesses.  Moving element bit 2 above the six lane bits makes each of those
+// accesses contiguous across the wave (lane stride 16 bytes): no padding, no bank conflicts.
+constexpr unsigned lds_phys_rot(unsigned i) {
+    return (i & 3u) | (((i >> 3) & 63u) << 2) | (((i >> 2) & 1u) << 8) | (i & ~511u);
+}
 
 }  // namespace wht
