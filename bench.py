@@ -26,8 +26,9 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published peak
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=150,
+                    help="untimed steps first; the GPU needs ~100 steps to settle its clocks under this load")
     ap.add_argument("--workload", default="C5_large")
     ap.add_argument("--no-extras", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")

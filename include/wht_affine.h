@@ -28,8 +28,9 @@
  *     exactly; partial overlap is undefined.
  *   - The return value is a wht_status_t.  Arguments are validated before anything is enqueued, so
  *     a failed call has no side effects.  N = 0 is valid (backward then zero-fills dalpha, dbeta).
- *   - d must be a power of two with WHT_MIN_D <= d <= WHT_MAX_D; anything else (including the
- *     paper's own d = 768 and 1536, for which it does not say how H is built) is WHT_ERR_BAD_DIM.
+ *   - d must be a power of two with WHT_MIN_D <= d <= WHT_MAX_D (WHT_MAX_D_F32 for float32
+ *     tensors, whose token groups take twice the LDS); anything else (including the paper's own
+ *     d = 768 and 1536, for which it does not say how H is built) is WHT_ERR_BAD_DIM.
  */
 #ifndef WHT_AFFINE_H
 #define WHT_AFFINE_H
@@ -42,7 +43,8 @@ extern "C" {
 #endif
 
 #define WHT_MIN_D 32
-#define WHT_MAX_D 16384
+#define WHT_MAX_D 16384        /* bfloat16 tensors */
+#define WHT_MAX_D_F32 8192     /* float32 tensors */
 
 typedef enum {
     WHT_DTYPE_F32  = 0,   /* x, y, dy, dx are IEEE binary32 */
@@ -52,7 +54,7 @@ typedef enum {
 typedef enum {
     WHT_OK             = 0,
     WHT_ERR_NULL_PTR   = 1,   /* a required pointer is NULL */
-    WHT_ERR_BAD_DIM    = 2,   /* d not a power of two in [WHT_MIN_D, WHT_MAX_D], or N < 0 */
+    WHT_ERR_BAD_DIM    = 2,   /* d not a power of two in [WHT_MIN_D, WHT_MAX_D(_F32)], or N < 0 */
     WHT_ERR_BAD_DTYPE  = 3,
     WHT_ERR_MISALIGNED = 4,   /* a tensor pointer is not 16-byte aligned */
     WHT_ERR_WORKSPACE  = 5,   /* workspace NULL or smaller than wht_affine_backward_workspace_bytes */

@@ -25,7 +25,7 @@ static int env_int(const char* name, int fallback) {
     return (x >= 1 && x <= 64) ? x : fallback;
 }
 static int groups_per_cu(bool backward) {
-    static const int fwd = env_int("WHT_AFFINE_FWD_GROUPS_PER_CU", 4);
+    static const int fwd = env_int("WHT_AFFINE_FWD_GROUPS_PER_CU", 8);
     static const int bwd = env_int("WHT_AFFINE_BWD_GROUPS_PER_CU", 2);
     return backward ? bwd : fwd;
 }
@@ -37,23 +37,11 @@ static int grid_for(int64_t N, bool backward) {
     return (int)(groups < cap ? groups : cap);
 }
 
-// Workgroups of the largest d need more than the 64 KiB of LDS a kernel may use by default.
-template <class C, class K>
-static bool allow_lds(K kernel) {
-    if constexpr (C::kLdsBytes > 64u * 1024u) {
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)C::kLdsBytes) == hipSuccess;
-    }
-    return true;
-}
-
 template <class C>
 static int launch_forward(const void* x, const float* alpha, const float* beta, void* y, int64_t N,
                           hipStream_t stream) {
     using T = typename C::io::elem_t;
-    if (!allow_lds<C>(forward_kernel<C>)) return WHT_ERR_LAUNCH;
-    hipLaunchKernelGGL(forward_kernel<C>, dim3(grid_for<C>(N, false)), dim3(C::BT), C::kLdsBytes, stream,
+    hipLaunchKernelGGL(forward_kernel<C>, dim3(grid_for<C>(N, false)), dim3(C::BT), 0, stream,
                        static_cast<const T*>(x), alpha, beta, static_cast<T*>(y), N);
     return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
 }
@@ -63,8 +51,7 @@ static int launch_backward(const void* dy, const void* x, const float* alpha, vo
                            float* dbeta, int64_t N, void* workspace, hipStream_t stream) {
     using T = typename C::io::elem_t;
     const int grid = grid_for<C>(N, true);
-    if (!allow_lds<C>(backward_kernel<C>)) return WHT_ERR_LAUNCH;
-    hipLaunchKernelGGL(backward_kernel<C>, dim3(grid), dim3(C::BT), C::kLdsBytes, stream,
+    hipLaunchKernelGGL(backward_kernel<C>, dim3(grid), dim3(C::BT), 0, stream,
                        static_cast<const T*>(dy), static_cast<const T*>(x), alpha, static_cast<T*>(dx),
                        static_cast<float*>(workspace), N);
     if (hipGetLastError() != hipSuccess) return WHT_ERR_LAUNCH;
@@ -125,7 +112,9 @@ static int dispatch_d(int logd, Op op, Args& a) {
     case 11: return run_d<Io, 11>(op, a);
     case 12: return run_d<Io, 12>(op, a);
     case 13: return run_d<Io, 13>(op, a);
-    case 14: return run_d<Io, 14>(op, a);
+    case 14:
+        if constexpr (std::is_same<Io, IoBF16>::value) return run_d<Io, 14>(op, a);
+        return WHT_ERR_BAD_DIM;
     default: return WHT_ERR_BAD_DIM;
     }
 }
@@ -147,6 +136,7 @@ static int check_dims(int64_t N, int32_t d, int32_t dtype, int* logd) {
     if (dtype != WHT_DTYPE_F32 && dtype != WHT_DTYPE_BF16) return WHT_ERR_BAD_DTYPE;
     *logd = log2_exact(d);
     if (*logd < 0 || N < 0) return WHT_ERR_BAD_DIM;
+    if (dtype == WHT_DTYPE_F32 && d > WHT_MAX_D_F32) return WHT_ERR_BAD_DIM;
     return WHT_OK;
 }
 
@@ -223,7 +213,7 @@ const char* wht_affine_status_string(int status) {
     switch (status) {
     case WHT_OK:             return "ok";
     case WHT_ERR_NULL_PTR:   return "a required pointer is NULL";
-    case WHT_ERR_BAD_DIM:    return "d must be a power of two in [WHT_MIN_D, WHT_MAX_D] and N >= 0";
+    case WHT_ERR_BAD_DIM:    return "d must be a power of two in [WHT_MIN_D, WHT_MAX_D] (WHT_MAX_D_F32 for float32) and N >= 0";
     case WHT_ERR_BAD_DTYPE:  return "dtype must be WHT_DTYPE_F32 or WHT_DTYPE_BF16";
     case WHT_ERR_MISALIGNED: return "tensor pointers must be 16-byte aligned";
     case WHT_ERR_WORKSPACE:  return "workspace is NULL or smaller than wht_affine_backward_workspace_bytes";

@@ -101,8 +101,11 @@ struct Cfg {
     static constexpr int G = BT / TPT;          // tokens per workgroup pass
     static constexpr unsigned phys(unsigned i) { return lds_phys(i); }
     static constexpr unsigned kTokenWords = lds_words_skew(D);
-    static constexpr unsigned kLdsBytes = (P > 1 || G > 1) ? G * kTokenWords * 4u : 16u;
-    static_assert(kLdsBytes <= 160u * 1024u, "token group does not fit LDS");
+    static constexpr unsigned kExchangeBytes = (P > 1 || G > 1) ? G * kTokenWords * 4u : 16u;
+    static constexpr unsigned kStageBytes = BT * NV * 16u;          // one tensor's token group, as stored
+    static constexpr unsigned kLdsBytes = kExchangeBytes + kStageBytes;              // forward
+    static constexpr unsigned kLdsBytesBackward = kExchangeBytes + 2u * kStageBytes; // x and dy
+    static_assert(kLdsBytesBackward <= 160u * 1024u, "token group does not fit LDS");
 };
 
 // Matrix-core schedule (bfloat16 I/O, d >= 1024): 2^LOGT MFMA tiles of 1024 elements per wave.
@@ -127,8 +130,11 @@ struct MfmaCfg {
     static constexpr int G = BT / TPT;
     static constexpr unsigned phys(unsigned i) { return lds_phys_rot(i); }
     static constexpr unsigned kTokenWords = D;
-    static constexpr unsigned kLdsBytes = (P > 1 || G > 1) ? G * kTokenWords * 4u : 16u;
-    static_assert(kLdsBytes <= 160u * 1024u, "token group does not fit LDS");
+    static constexpr unsigned kExchangeBytes = (P > 1 || G > 1) ? G * kTokenWords * 4u : 16u;
+    static constexpr unsigned kStageBytes = BT * NV * 16u;          // one tensor's token group, as stored
+    static constexpr unsigned kLdsBytes = kExchangeBytes + kStageBytes;              // forward
+    static constexpr unsigned kLdsBytesBackward = kExchangeBytes + 2u * kStageBytes; // x and dy
+    static_assert(kLdsBytesBackward <= 160u * 1024u, "token group does not fit LDS");
 };
 
 // Element offset of thread t (within its token) in phase PH.
@@ -222,6 +228,16 @@ struct ThreadMap {
 //   otherwise the phases run in reverse (enter in the last layout, leave in the first) -- the
 //   backward pass uses this so that dy can be consumed in the layout z was produced in.
 // Ends with a workgroup barrier when LDS was used, so the caller may reuse LDS at once.
+// Workgroup barrier for the LDS exchange.  __syncthreads() carries a release/acquire fence that
+// makes the wave wait for *all* its outstanding memory operations -- including the prefetches in
+// flight and the stores of the previous token, which have nothing to do with the exchange.  The
+// exchange only needs this wave's LDS writes to have completed (lgkmcnt) before the barrier.
+__device__ __forceinline__ void exchange_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 template <class C, bool FORWARD_ORDER>
 __device__ __forceinline__ void transform(float (&r)[C::E], float* lds, const ThreadMap<C>& tm) {
     static_for<0, C::P>([&](auto s) {
@@ -233,22 +249,76 @@ __device__ __forceinline__ void transform(float (&r)[C::E], float* lds, const Th
             // a middle phase rewrites exactly the words it read, so only the hand-over to the
             // next layout needs the barrier
             lds_put<C, PH>(r, lds + tm.lds_off[PH]);
-            __syncthreads();
+            exchange_barrier();
         }
     });
-    if constexpr (C::P > 1) __syncthreads();
+    if constexpr (C::P > 1) exchange_barrier();
 }
 
-// Global <-> registers in the layout of phase PH (first or last): 16 bytes per lane per access.
+// Global -> LDS staging -> registers.  x and dy are fetched with LDS-direct loads (the data goes
+// from memory into LDS without passing through registers), a whole iteration before they are used,
+// so that tens of KiB per workgroup are in flight at all times at no register cost.  An LDS-direct
+// load of 16 bytes writes lane l's vector to (wave-uniform base) + 16*l: every wave owns a private
+// 1 KiB slot per vector, reads back exactly what it fetched, and needs no workgroup barrier --
+// only its own vmcnt (loads return in issue order) and lgkmcnt waits, which are written out here
+// because the compiler does not track the dependence between an LDS-direct load and a later LDS read.
+typedef const __attribute__((address_space(1))) void* global_cptr;
+typedef __attribute__((address_space(3))) void* lds_ptr;
+
 template <class C, int PH>
-__device__ __forceinline__ void global_get(float (&r)[C::E], const typename C::io::elem_t* row,
-                                           unsigned thread_elem, bool active) {
+__device__ __forceinline__ void stage_issue(unsigned char* wave_slot, const typename C::io::elem_t* row,
+                                            unsigned thread_elem) {
     static_for<0, C::NV>([&](auto c) {
         constexpr int Cc = decltype(c)::value;
         constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V);
-        uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-        if (active) raw = stream_load16(row + thread_elem + off);
-        C::io::unpack(raw, &r[Cc * C::V]);
+        __builtin_amdgcn_global_load_lds((global_cptr)(row + thread_elem + off),
+                                         (lds_ptr)(wave_slot + Cc * 1024), 16, 0, 0);
+    });
+}
+
+// Read the staged vectors back.  Written as inline assembly on purpose: for a compiler-visible
+// LDS load the waitcnt insertion would wait for *every* LDS-direct load in flight (vmcnt(0)),
+// including the next group's prefetch issued moments ago.  Which loads must have landed is known
+// here (wait_vmem below, issued by the caller first); the reads' own completion is awaited inside
+// this function, with the values tied to the wait so that no use can be scheduled before it.
+__device__ __forceinline__ unsigned lds_byte_address(const void* p) {
+    return (unsigned)(size_t)(const __attribute__((address_space(3))) unsigned char*)p;
+}
+
+template <class C>
+__device__ __forceinline__ void stage_read(uint4 (&raw)[C::NV], const unsigned char* wave_slot) {
+    static_assert(C::NV == 1 || C::NV == 2 || C::NV == 4 || C::NV == 8, "unexpected vector count");
+    const unsigned addr = lds_byte_address(wave_slot) + (threadIdx.x & 63u) * 16u;
+    u32x4 v[C::NV];
+#pragma unroll
+    for (int c = 0; c < C::NV; ++c) {
+        const unsigned a = addr + c * 1024;
+        asm volatile("ds_read_b128 %0, %1" : "=&v"(v[c]) : "v"(a) : "memory");
+    }
+    if constexpr (C::NV == 1)
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v[0]) : : "memory");
+    else if constexpr (C::NV == 2)
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v[0]), "+v"(v[1]) : : "memory");
+    else if constexpr (C::NV == 4)
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]) : : "memory");
+    else
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7])
+                     : : "memory");
+#pragma unroll
+    for (int c = 0; c < C::NV; ++c) raw[c] = make_uint4(v[c].x, v[c].y, v[c].z, v[c].w);
+}
+
+// Wait until at most PENDING of this wave's vector-memory operations are outstanding.
+template <int PENDING>
+__device__ __forceinline__ void wait_vmem() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory");
+}
+template <class C>
+__device__ __forceinline__ void unpack_all(float (&r)[C::E], const uint4 (&raw)[C::NV]) {
+    static_for<0, C::NV>([&](auto c) {
+        constexpr int Cc = decltype(c)::value;
+        C::io::unpack(raw[Cc], &r[Cc * C::V]);
     });
 }
 
@@ -274,18 +344,6 @@ __device__ __forceinline__ void param_get(float (&r)[C::E], const float* p, unsi
     });
 }
 
-// 16-byte global vectors as loaded, no widening (they are MFMA A operands as they stand).
-template <class C, int PH>
-__device__ __forceinline__ void global_get_raw(uint4 (&raw)[C::NV], const typename C::io::elem_t* row,
-                                               unsigned thread_elem, bool active) {
-    static_for<0, C::NV>([&](auto c) {
-        constexpr int Cc = decltype(c)::value;
-        constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V);
-        raw[Cc] = make_uint4(0u, 0u, 0u, 0u);
-        if (active) raw[Cc] = stream_load16(row + thread_elem + off);
-    });
-}
-
 // ------------------------------------------------------------------------------------------------
 // matrix-core rounds: H_32 along five element bits as a 32x32x32 product with a +-1 matrix
 //
@@ -303,6 +361,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 struct HadamardB {
     bf16x8 k_lo, k_hi;      // B operand of the first / second K-half
+    uint32_t minus_first, minus_second;   // bf16 pairs (-1, 0) and (0, -1), see hadamard_round_f32
 };
 
 __device__ __forceinline__ HadamardB make_hadamard_b() {
@@ -322,6 +381,10 @@ __device__ __forceinline__ HadamardB make_hadamard_b() {
     HadamardB b;
     b.k_lo = __builtin_bit_cast(bf16x8, make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]));
     b.k_hi = __builtin_bit_cast(bf16x8, make_uint4(w[1][0], w[1][1], w[1][2], w[1][3]));
+    // Kept opaque to the compiler so that they stay register operands: as an inline constant the
+    // (-1, 0) pair is encoded in a form the bf16 dot instruction reads differently.
+    asm volatile("s_mov_b32 %0, 0xbf80" : "=s"(b.minus_first));
+    asm volatile("s_mov_b32 %0, 0xbf800000" : "=s"(b.minus_second));
     return b;
 }
 
@@ -337,15 +400,20 @@ __device__ __forceinline__ f32x16 hadamard_round_bf16(const uint4& a_lo, const u
 
 // One round on float32 data: each value is split into bf16 hi + bf16 lo (hi = RNE(v), lo =
 // RNE(v - hi); v - hi is exact, so |v - hi - lo| <= 2^-18 |v|) and both parts go through the same
-// +-1 product, accumulated in float32.
+// +-1 product, accumulated in float32.  v - hi is formed without widening hi first: the bf16 dot
+// product  hi.first * (-1) + hi.second * 0 + v  is that difference, exactly.
 __device__ __forceinline__ f32x16 hadamard_round_f32(const float* v, const HadamardB& b) {
     uint32_t hi[8], lo[8];
+    const bf16x2 sel0 = __builtin_bit_cast(bf16x2, b.minus_first);
+    const bf16x2 sel1 = __builtin_bit_cast(bf16x2, b.minus_second);
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
         const uint32_t h = IoBF16::pack2(v[2 * p], v[2 * p + 1]);
-        const float h0 = __uint_as_float(h << 16), h1 = __uint_as_float(h & 0xffff0000u);
+        const bf16x2 hp = __builtin_bit_cast(bf16x2, h);
+        const float l0 = __builtin_amdgcn_fdot2_f32_bf16(hp, sel0, v[2 * p], false);
+        const float l1 = __builtin_amdgcn_fdot2_f32_bf16(hp, sel1, v[2 * p + 1], false);
         hi[p] = h;
-        lo[p] = IoBF16::pack2(v[2 * p] - h0, v[2 * p + 1] - h1);
+        lo[p] = IoBF16::pack2(l0, l1);
     }
     f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     const bf16x8 lo0 = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
@@ -390,18 +458,13 @@ __device__ __forceinline__ void mfma_rounds_from_f32(float (&r)[C::E], const Had
     });
 }
 
-// x[tok] -> H_raw x in the last layout, whichever schedule C is.
+// raw x[tok] (first layout) -> H_raw x in the last layout, whichever schedule C is.
 template <class C>
-__device__ __forceinline__ void load_and_transform(float (&r)[C::E], const typename C::io::elem_t* row,
+__device__ __forceinline__ void transform_from_raw(float (&r)[C::E], const uint4 (&raw)[C::NV],
                                                    float* lds, const ThreadMap<C>& tm,
-                                                   const HadamardB& b, bool active) {
-    if constexpr (C::kMfma) {
-        uint4 raw[C::NV];
-        global_get_raw<C, 0>(raw, row, tm.first_elem, active);
-        mfma_rounds_from_bf16<C>(r, raw, b);
-    } else {
-        global_get<C, 0>(r, row, tm.first_elem, active);
-    }
+                                                   const HadamardB& b) {
+    if constexpr (C::kMfma) mfma_rounds_from_bf16<C>(r, raw, b);
+    else                    unpack_all<C>(r, raw);
     transform<C, true>(r, lds, tm);
 }
 
@@ -421,44 +484,84 @@ __device__ __forceinline__ float inv_sqrt_d() {
 }
 
 // ------------------------------------------------------------------------------------------------
-// forward:  y = (alpha / sqrt d) (.) (H_raw x) + beta
+// Kernels.  A workgroup holds G token slots of TPT threads each and strides over token groups
+// (persistent grid).  Inputs of group k+1 are in flight (LDS-direct loads) while group k is
+// computed.  A ragged last group re-reads the last token (clamped row) and masks its stores.
 
+template <class C>
+struct Walker {
+    int64_t N, groups;
+    unsigned slot;
+    __device__ __forceinline__ int64_t token(int64_t grp) const { return grp * C::G + slot; }
+    __device__ __forceinline__ int64_t row(int64_t grp) const {       // clamped: always a valid row
+        const int64_t tok = token(grp);
+        return tok < N ? tok : N - 1;
+    }
+};
+
+// forward:  y = (alpha / sqrt d) (.) (H_raw x) + beta
+//
+// Per iteration k (x(k) has landed in its stage):
+//   raw <- stage;  issue x(k+1) -> stage;  transform raw;  affine;  wait for everything pending;
+//   store y(k).
+// The one wait sits just before the stores of y(k): all it can be waiting for is x(k+1), issued a
+// whole transform earlier, and the stores of y(k-1), a whole iteration old.  (Loads and stores may
+// complete out of order with respect to each other, so a counted wait is only safe when nothing
+// but older loads is pending; waiting here, before the new stores, keeps it that way.)
 template <class C>
 __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::elem_t* x,
                                                         const float* __restrict__ alpha,
                                                         const float* __restrict__ beta,
                                                         typename C::io::elem_t* y,
                                                         int64_t N) {
-    extern __shared__ __align__(16) float lds[];
+    // separate LDS objects: the compiler can then tell that the exchange region's accesses never
+    // alias an LDS-direct load in flight, and does not wait for the prefetch before them
+    __shared__ __align__(16) float lds[C::kExchangeBytes / 4];
+    __shared__ __align__(16) unsigned char stage_buf[C::kStageBytes];
     constexpr int LAST = C::P - 1;
-    const unsigned t = threadIdx.x % C::TPT, slot = threadIdx.x / C::TPT;
+    const unsigned t = threadIdx.x % C::TPT;
+    Walker<C> wk{N, (N + C::G - 1) / C::G, threadIdx.x / C::TPT};
     ThreadMap<C> tm;
-    tm.init(t, slot);
+    tm.init(t, wk.slot);
     HadamardB hb{};
     if constexpr (C::kMfma) hb = make_hadamard_b();
+    unsigned char* stage = stage_buf + (threadIdx.x >> 6) * (C::NV * 1024);
 
     float a[C::E], b[C::E];
     param_get<C, LAST>(a, alpha, tm.last_elem, inv_sqrt_d<C>());
     param_get<C, LAST>(b, beta, tm.last_elem, 1.0f);
 
-    const int64_t groups = (N + C::G - 1) / C::G;
-    for (int64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
-        const int64_t tok = grp * C::G + slot;
-        const bool active = tok < N;
+    const int64_t step = gridDim.x;
+    int64_t grp = blockIdx.x;
+    if (grp < wk.groups) {
+        stage_issue<C, 0>(stage, x + wk.row(grp) * C::D, tm.first_elem);
+        wait_vmem<0>();
+    }
+    for (; grp < wk.groups; grp += step) {
+        const bool more = grp + step < wk.groups;
+        uint4 raw[C::NV];
+        stage_read<C>(raw, stage);
+        if (more) stage_issue<C, 0>(stage, x + wk.row(grp + step) * C::D, tm.first_elem);
         float r[C::E];
-        load_and_transform<C>(r, x + tok * C::D, lds, tm, hb, active);
+        transform_from_raw<C>(r, raw, lds, tm, hb);
 #pragma unroll
         for (int i = 0; i < C::E; ++i) r[i] = fmaf(r[i], a[i], b[i]);
-        global_put<C, LAST>(r, y + tok * C::D, tm.last_elem, active);
+        if (more) wait_vmem<0>();
+        const int64_t tok = wk.token(grp);
+        global_put<C, LAST>(r, y + tok * C::D, tm.last_elem, tok < N);
     }
 }
 
-// ------------------------------------------------------------------------------------------------
 // backward:  z = H x (recomputed);  dalpha += dy z;  dbeta += dy;  dx = H_raw((alpha/sqrt d) dy)
-// Each workgroup walks a strided set of token groups, keeps its dalpha/dbeta sums in registers,
-// and at the end writes one row of partial sums; reduce_partials_kernel adds the rows in a fixed
-// order, so the result does not depend on scheduling.
-
+// Each workgroup keeps its dalpha/dbeta sums in registers and at the end writes one row of partial
+// sums; reduce_partials_kernel adds the rows in a fixed order, so the result does not depend on
+// scheduling.
+//
+// Per iteration k (x(k) and dy(k) have landed in their stages):
+//   raw <- stage X;  graw <- stage DY;  issue x(k+1), dy(k+1);  z = transform(raw);  sums;
+//   g = alpha' dy;  transform back;  wait for everything pending;  store dx(k).
+// As in the forward kernel the single wait precedes the stores and only covers loads issued a whole
+// iteration earlier (and the previous token's stores).
 template <class C>
 __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::elem_t* dy,
                                                          const typename C::io::elem_t* x,
@@ -466,26 +569,49 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
                                                          typename C::io::elem_t* dx,
                                                          float* __restrict__ partials,   // [grid][2][D]
                                                          int64_t N) {
-    extern __shared__ __align__(16) float lds[];
+    __shared__ __align__(16) float lds[C::kExchangeBytes / 4];
+    __shared__ __align__(16) unsigned char stage_x_buf[C::kStageBytes];
+    __shared__ __align__(16) unsigned char stage_g_buf[C::kStageBytes];
     constexpr int LAST = C::P - 1;
-    const unsigned t = threadIdx.x % C::TPT, slot = threadIdx.x / C::TPT;
+    const unsigned t = threadIdx.x % C::TPT;
+    Walker<C> wk{N, (N + C::G - 1) / C::G, threadIdx.x / C::TPT};
     ThreadMap<C> tm;
-    tm.init(t, slot);
+    tm.init(t, wk.slot);
     HadamardB hb{};
     if constexpr (C::kMfma) hb = make_hadamard_b();
+    unsigned char* stage_x = stage_x_buf + (threadIdx.x >> 6) * (C::NV * 1024);
+    unsigned char* stage_g = stage_g_buf + (threadIdx.x >> 6) * (C::NV * 1024);
 
     float a[C::E], da[C::E], db[C::E];
     param_get<C, LAST>(a, alpha, tm.last_elem, inv_sqrt_d<C>());
 #pragma unroll
     for (int i = 0; i < C::E; ++i) { da[i] = 0.0f; db[i] = 0.0f; }
 
-    const int64_t groups = (N + C::G - 1) / C::G;
-    for (int64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
-        const int64_t tok = grp * C::G + slot;
-        const bool active = tok < N;
+    const int64_t step = gridDim.x;
+    int64_t grp = blockIdx.x;
+    if (grp < wk.groups) {
+        stage_issue<C, 0>(stage_x, x + wk.row(grp) * C::D, tm.first_elem);
+        stage_issue<C, LAST>(stage_g, dy + wk.row(grp) * C::D, tm.last_elem);
+        wait_vmem<0>();
+    }
+    for (; grp < wk.groups; grp += step) {
+        const bool more = grp + step < wk.groups;
+        uint4 raw[C::NV], graw[C::NV];
+        stage_read<C>(raw, stage_x);
+        stage_read<C>(graw, stage_g);
+        if (more) {
+            stage_issue<C, 0>(stage_x, x + wk.row(grp + step) * C::D, tm.first_elem);
+            stage_issue<C, LAST>(stage_g, dy + wk.row(grp + step) * C::D, tm.last_elem);
+        }
         float r[C::E], g[C::E];
-        load_and_transform<C>(r, x + tok * C::D, lds, tm, hb, active);   // r = H_raw x, last layout
-        global_get<C, LAST>(g, dy + tok * C::D, tm.last_elem, active);
+        transform_from_raw<C>(r, raw, lds, tm, hb);           // r = H_raw x, last layout
+        unpack_all<C>(g, graw);
+        const int64_t tok = wk.token(grp);
+        const bool active = tok < N;
+        if (!active) {                                        // ragged last group: contribute nothing
+#pragma unroll
+            for (int i = 0; i < C::E; ++i) g[i] = 0.0f;
+        }
 #pragma unroll
         for (int i = 0; i < C::E; ++i) {
             da[i] = fmaf(g[i], r[i], da[i]);                  // 1/sqrt d applied once at the end
@@ -493,6 +619,7 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
             g[i] *= a[i];
         }
         transform_back<C>(g, lds, tm, hb);                    // g = H_raw(alpha' dy), first layout
+        if (more) wait_vmem<0>();
         global_put<C, 0>(g, dx + tok * C::D, tm.first_elem, active);
     }
 

@@ -59,6 +59,8 @@ ALL_D = [32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384]
 @pytest.mark.parametrize("d", ALL_D)
 def test_forward_every_d(d, dtype):
     # N chosen so that the last workgroup pass is ragged for every tokens-per-workgroup value
+    if dtype == "f32" and d > 8192:
+        pytest.skip("float32 tensors are limited to WHT_MAX_D_F32 = 8192")
     N = 67 if d <= 2048 else 9
     _announce(f"forward d={d} {dtype} N={N}")
     check_forward_full(synth.make_inputs(N, d, dtype, seed=d, backward=False), f"fwd d={d} {dtype}")
@@ -67,6 +69,8 @@ def test_forward_every_d(d, dtype):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("d", ALL_D)
 def test_backward_every_d(d, dtype):
+    if dtype == "f32" and d > 8192:
+        pytest.skip("float32 tensors are limited to WHT_MAX_D_F32 = 8192")
     N = 67 if d <= 2048 else 9
     _announce(f"backward d={d} {dtype} N={N}")
     check_backward_full(synth.make_inputs(N, d, dtype, seed=d + 1), f"bwd d={d} {dtype}")

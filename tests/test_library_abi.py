@@ -30,6 +30,7 @@ def test_library_exports_every_declared_symbol():
 def test_version_and_status_strings():
     assert binding.wht_affine_version() >= 100
     seen = {binding.wht_affine_status_string(s) for s in range(0, 7)}
+    assert binding.wht_affine_status_string(2).startswith("d must be a power of two")
     assert len(seen) == 7 and "ok" in seen
     assert binding.wht_affine_status_string(99) == "unknown status"
 
@@ -46,7 +47,8 @@ P = 0x1000   # a 16-byte-aligned non-null fake address: validation fails before 
     ((P, P, P, P, 4, 768, 1), DIM),        # the paper's own non-power-of-two width: rejected
     ((P, P, P, P, 4, 1536, 1), DIM),
     ((P, P, P, P, 4, 16, 0), DIM),         # below WHT_MIN_D
-    ((P, P, P, P, 4, 32768, 0), DIM),      # above WHT_MAX_D
+    ((P, P, P, P, 4, 32768, 1), DIM),      # above WHT_MAX_D
+    ((P, P, P, P, 4, 16384, 0), DIM),      # above WHT_MAX_D_F32
     ((P, P, P, P, 4, 0, 0), DIM),
     ((P, P, P, P, 4, -256, 0), DIM),
     ((P, P, P, P, -1, 256, 0), DIM),
