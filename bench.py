@@ -233,11 +233,26 @@ def decode_latency(torch, wht, synth, iters=1000):
     return rows
 
 
+def recorded_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` as measured with rocprofv3 counters
+    (FETCH_SIZE + WRITE_SIZE, calibrated on the copy kernel) and recorded in the committed summary
+    under profiles/; None when no such record exists."""
+    import glob
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        for line in open(path):
+            if "TRAFFIC_JSON" in line:
+                rec = json.loads(line.split("TRAFFIC_JSON", 1)[1])
+                if rec.get("workload") == workload and rec.get("kernel") == kernel:
+                    return rec["traffic_bytes_per_launch"]
+    return None
+
+
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (tokens are independent; "
-              "see DESIGN.md for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py measures one GPU: this build has no multi-GPU path (tokens are independent, so "
+              "the layer shards by splitting N; only dalpha/dbeta would need an all-reduce). "
+              "Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
     import paper_2603_08343_amd as wht
@@ -252,6 +267,7 @@ def main():
     bench = Bench(torch, wht, synth, args.workload)
     step_ms, fwd_ms, bwd_ms = bench.run(args.steps, args.warmup)
     head = summarize(w, step_ms, fwd_ms, bwd_ms)
+    sets = bench.sets
     del bench
     torch.cuda.empty_cache()
 
@@ -262,7 +278,8 @@ def main():
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "backward_kernel (+ reduce_partials_kernel)" if w.backward else "forward_kernel",
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": None, "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms}
+                "traffic": recorded_traffic(w.name, "backward_kernel" if w.backward else "forward_kernel"),
+                "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms}
 
     result = {
         "metric": "wht_affine_fwd_bwd_tokens_per_s" if w.backward else "wht_affine_fwd_tokens_per_s",
@@ -271,7 +288,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: N={w.N} tokens, d={w.d}, {w.dtype} I/O with f32 arithmetic, "
                                f"{'forward+backward' if w.backward else 'forward'}",
-                   "buffer_sets_rotated": None},
+                   "io_dtype": w.dtype, "buffer_sets_rotated": sets},
         "roofline": roofline,
         "headline": head,
     }

@@ -1,11 +1,15 @@
-// Host-side self-test of the transform schedule (wht_plan.h), compiled with the host compiler only.
-// For every (log2 d, log2 values-per-thread, log2 vector) the library instantiates it checks that
-//   - every butterfly stage runs exactly once and only on register-resident bits,
+// Host-side self-test of the transform schedules (wht_plan.h), compiled with the host compiler only.
+// For every (schedule, log2 d) the library instantiates it checks that
+//   - every stage runs exactly once (matrix-core bits included) and only on register-resident bits,
 //   - in every phase (thread, register) -> element is a bijection onto [0, d),
-//   - the LDS address map is injective, 16-byte-group preserving and inside the token's region,
-//   - the first and last phases give each lane whole 16-byte vectors, contiguous across lanes,
-// and it emulates the whole schedule on the CPU (registers + an LDS array, phase by phase, forward
-// and reverse order) against a direct +-1 sum on small sizes.
+//   - the LDS address map is injective, keeps 16-byte groups together, is additive over disjoint
+//     bit sets and stays inside the token's region,
+//   - the first and last phases give each lane whole 16-byte vectors, contiguous across >= 8 lanes,
+//   - for the matrix-core schedule, the first layout is the MFMA operand layout the kernels assume
+//     (registers = bits 0,1,2,9,tile bits; lanes = bits 3..8),
+// and it emulates the whole schedule on the CPU (registers + an LDS array, phase by phase, in forward
+// and in reverse order, the matrix-core rounds as butterflies on their bits) against a direct +-1
+// sum on small sizes.
 // Prints one line per configuration; exit status 0 iff all pass.
 #include <cmath>
 #include <cstdio>
@@ -16,33 +20,48 @@
 
 using namespace wht;
 
+typedef unsigned (*PhysFn)(unsigned);
+static unsigned phys_skew(unsigned i) { return lds_phys(i); }
+static unsigned phys_rot(unsigned i) { return lds_phys_rot(i); }
+
 static unsigned thread_elem(const PhaseDesc& p, int n, int e, unsigned t) {
     unsigned off = 0;
     for (int k = 0; k < n - e; ++k) off |= ((t >> k) & 1u) << p.tb[k];
     return off;
 }
 
-static bool check(int n, int e, int v) {
-    const PlanDesc pl = make_plan(n, e, v);
+static void butterfly_bits(std::vector<double>& a, unsigned bits) {
+    const unsigned D = (unsigned)a.size();
+    for (unsigned b = 0; (1u << b) < D; ++b) {
+        if (!((bits >> b) & 1u)) continue;
+        for (unsigned i = 0; i < D; ++i)
+            if (!((i >> b) & 1u)) {
+                const double u = a[i], w = a[i | (1u << b)];
+                a[i] = u + w; a[i | (1u << b)] = u - w;
+            }
+    }
+}
+
+static bool check(const char* kind, const PlanDesc& pl, PhysFn phys, unsigned words, bool verbose) {
+    const int n = pl.n, e = pl.e, v = pl.v;
     const unsigned D = 1u << n, E = 1u << e, T = 1u << (n - e);
     bool ok = plan_is_complete(pl);
-    const unsigned words = (lds_phys(D - 1) + 1 + 3) & ~3u;
     // address map
     std::vector<char> used(words, 0);
     for (unsigned i = 0; i < D; ++i) {
-        unsigned a = lds_phys(i);
+        const unsigned a = phys(i);
         if (a >= words || used[a]) ok = false; else used[a] = 1;
-        if ((i & 3u) == 0 && ((a & 3u) != 0 || lds_phys(i + 3) != a + 3)) ok = false;
+        if ((i & 3u) == 0 && ((a & 3u) != 0 || phys(i + 3) != a + 3)) ok = false;
     }
     for (int p = 0; p < pl.nphase; ++p) {
         std::vector<char> seen(D, 0);
         for (unsigned t = 0; t < T; ++t)
             for (unsigned r = 0; r < E; ++r) {
-                unsigned a = thread_elem(pl.ph[p], n, e, t), b = reg_elem_offset(pl.ph[p], e, (int)r);
+                const unsigned a = thread_elem(pl.ph[p], n, e, t), b = reg_elem_offset(pl.ph[p], e, (int)r);
                 if (a & b) ok = false;
-                unsigned el = a | b;
+                const unsigned el = a | b;
                 if (el >= D || seen[el]) ok = false; else seen[el] = 1;
-                if (lds_phys(el) != lds_phys(a) + lds_phys(b)) ok = false;
+                if (phys(el) != phys(a) + phys(b)) ok = false;
             }
     }
     // global layouts: vector bits in the low register bits, low thread bits follow on
@@ -52,16 +71,33 @@ static bool check(int n, int e, int v) {
         while (run < n - e && pl.ph[p].tb[run] == v + run) ++run;
         if (n - e > 0 && run < ((n - e) < 3 ? (n - e) : 3)) ok = false;   // >= 128 contiguous bytes
     }
+    if (pl.mfma_bits) {
+        // operand layout of the matrix-core rounds
+        const PhaseDesc& f = pl.ph[0];
+        if (pl.mfma_bits != 0x3ffu || v != 3) ok = false;
+        if (f.rb[0] != 0 || f.rb[1] != 1 || f.rb[2] != 2 || f.rb[3] != 9) ok = false;
+        for (int q = 4; q < e; ++q) if (f.rb[q] != 10 + (q - 4)) ok = false;
+        for (int k = 0; k < 6; ++k) if (f.tb[k] != 3 + k) ok = false;
+        // every layout keeps lanes on bits 3..8, so the exchange is between waves only
+        for (int p = 0; p < pl.nphase; ++p)
+            for (int k = 0; k < 6; ++k) if (pl.ph[p].tb[k] != 3 + k) ok = false;
+    }
     // emulate on the CPU for small d
-    if (n <= 11) {
+    if (n <= 12) {
         for (int reverse = 0; reverse < 2; ++reverse) {
             std::vector<double> x(D), lds(words, NAN), want(D);
             for (unsigned i = 0; i < D; ++i) x[i] = std::sin(0.37 * i + 1.0) + (i % 7) * 0.25;
-            for (unsigned j = 0; j < D; ++j) {
-                double s = 0;
-                for (unsigned k = 0; k < D; ++k) s += (__builtin_popcount(j & k) & 1) ? -x[k] : x[k];
-                want[j] = s;
+            want = x;
+            butterfly_bits(want, D - 1);
+            if (n <= 9) {       // and the direct sum itself on the smallest sizes
+                for (unsigned j = 0; j < D; ++j) {
+                    double s = 0;
+                    for (unsigned k = 0; k < D; ++k) s += (__builtin_popcount(j & k) & 1) ? -x[k] : x[k];
+                    if (std::fabs(s - want[j]) > 1e-9 * (1 + std::fabs(s))) ok = false;
+                }
             }
+            // the matrix-core rounds come first going forward (on the data as loaded) ...
+            if (!reverse) butterfly_bits(x, pl.mfma_bits);
             std::vector<std::vector<double>> reg(T, std::vector<double>(E));
             for (int s = 0; s < pl.nphase; ++s) {
                 const int p = reverse ? pl.nphase - 1 - s : s;
@@ -70,13 +106,13 @@ static bool check(int n, int e, int v) {
                     const unsigned base = thread_elem(ph, n, e, t);
                     for (unsigned r = 0; r < E; ++r) {
                         const unsigned el = base | reg_elem_offset(ph, e, (int)r);
-                        reg[t][r] = (s == 0) ? x[el] : lds[lds_phys(el)];
+                        reg[t][r] = (s == 0) ? x[el] : lds[phys(el)];
                     }
                     for (int q = 0; q < e; ++q) {
                         if (!((ph.stages >> ph.rb[q]) & 1u)) continue;
                         for (unsigned r = 0; r < E; ++r)
                             if (!((r >> q) & 1u)) {
-                                double a = reg[t][r], b = reg[t][r | (1u << q)];
+                                const double a = reg[t][r], b = reg[t][r | (1u << q)];
                                 reg[t][r] = a + b; reg[t][r | (1u << q)] = a - b;
                             }
                     }
@@ -85,23 +121,31 @@ static bool check(int n, int e, int v) {
                 for (unsigned t = 0; t < T; ++t) {
                     const unsigned base = thread_elem(ph, n, e, t);
                     for (unsigned r = 0; r < E; ++r)
-                        lds[lds_phys(base | reg_elem_offset(ph, e, (int)r))] = reg[t][r];
+                        lds[phys(base | reg_elem_offset(ph, e, (int)r))] = reg[t][r];
                 }
             }
+            std::vector<double> got(D);
+            for (unsigned j = 0; j < D; ++j) got[j] = lds[phys(j)];
+            // ... and last in reverse (on the registers of the first layout)
+            if (reverse) butterfly_bits(got, pl.mfma_bits);
             double worst = 0, big = 0;
             for (unsigned j = 0; j < D; ++j) {
-                worst = std::fmax(worst, std::fabs(lds[lds_phys(j)] - want[j]));
+                worst = std::fmax(worst, std::fabs(got[j] - want[j]));
                 big = std::fmax(big, std::fabs(want[j]));
             }
             if (!(worst <= 1e-9 * big)) ok = false;
         }
     }
-    std::printf("n=%2d e=%d v=%d phases=%d lds_words=%u %s\n", n, e, v, pl.nphase, words, ok ? "ok" : "FAIL");
-    for (int p = 0; p < pl.nphase && !ok; ++p) {
-        std::printf("   phase %d regs:", p);
-        for (int q = 0; q < e; ++q) std::printf(" %d", pl.ph[p].rb[q]);
-        std::printf("  stages mask 0x%x\n", pl.ph[p].stages);
-    }
+    std::printf("%-9s n=%2d e=%d v=%d phases=%d lds_words=%u %s\n", kind, n, e, v, pl.nphase, words,
+                ok ? "ok" : "FAIL");
+    if (verbose || !ok)
+        for (int p = 0; p < pl.nphase; ++p) {
+            std::printf("   phase %d regs:", p);
+            for (int q = 0; q < e; ++q) std::printf(" %d", pl.ph[p].rb[q]);
+            std::printf("  stages 0x%x  threads:", pl.ph[p].stages);
+            for (int k = 0; k < n - e; ++k) std::printf(" %d", pl.ph[p].tb[k]);
+            std::printf("\n");
+        }
     return ok;
 }
 
@@ -109,18 +153,13 @@ int main(int argc, char** argv) {
     bool ok = true;
     const bool verbose = argc > 1;
     for (int v : {2, 3})
-        for (int n = 5; n <= 14; ++n) {
-            ok = check(n, log_e_for(n, v), v) && ok;
-            if (verbose) {
-                const PlanDesc pl = make_plan(n, log_e_for(n, v), v);
-                for (int p = 0; p < pl.nphase; ++p) {
-                    std::printf("   phase %d regs:", p);
-                    for (int q = 0; q < pl.e; ++q) std::printf(" %d", pl.ph[p].rb[q]);
-                    std::printf("  stages 0x%x  threads:", pl.ph[p].stages);
-                    for (int k = 0; k < n - pl.e; ++k) std::printf(" %d", pl.ph[p].tb[k]);
-                    std::printf("\n");
-                }
-            }
+        for (int n = 5; n <= (v == 2 ? 13 : 14); ++n) {
+            const PlanDesc pl = make_plan(n, log_e_for(n, v), v);
+            ok = check("butterfly", pl, phys_skew, lds_words_skew(1u << n), verbose) && ok;
         }
+    for (int n = 10; n <= 14; ++n) {
+        const PlanDesc pl = make_mfma_plan(n, mfma_log_tiles(n));
+        ok = check("mfma", pl, phys_rot, 1u << n, verbose) && ok;
+    }
     return ok ? 0 : 1;
 }

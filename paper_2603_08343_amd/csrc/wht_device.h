@@ -607,10 +607,12 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
         transform_from_raw<C>(r, raw, lds, tm, hb);           // r = H_raw x, last layout
         unpack_all<C>(g, graw);
         const int64_t tok = wk.token(grp);
-        const bool active = tok < N;
-        if (!active) {                                        // ragged last group: contribute nothing
+        const bool active = C::G == 1 || tok < N;             // one slot per workgroup: never ragged
+        if constexpr (C::G > 1) {
+            if (!active) {                                    // ragged last group: contribute nothing
 #pragma unroll
-            for (int i = 0; i < C::E; ++i) g[i] = 0.0f;
+                for (int i = 0; i < C::E; ++i) g[i] = 0.0f;
+            }
         }
 #pragma unroll
         for (int i = 0; i < C::E; ++i) {
