@@ -238,7 +238,7 @@ __device__ __forceinline__ void exchange_barrier() {
     asm volatile("" ::: "memory");
 }
 
-template <class C, bool FORWARD_ORDER>
+template <class C, bool FORWARD_ORDER, bool TRAILING_BARRIER>
 __device__ __forceinline__ void transform(float (&r)[C::E], float* lds, const ThreadMap<C>& tm) {
     static_for<0, C::P>([&](auto s) {
         constexpr int S = decltype(s)::value;
@@ -252,7 +252,11 @@ __device__ __forceinline__ void transform(float (&r)[C::E], float* lds, const Th
             exchange_barrier();
         }
     });
-    if constexpr (C::P > 1) exchange_barrier();
+    // The next write into the exchange region must not overtake other waves' reads of this one.
+    // When the next transform runs in the opposite order (the backward kernel alternates), its
+    // first write goes, thread by thread, to exactly the words this thread has just read, and no
+    // barrier is needed; a kernel that only runs forward-order transforms needs it.
+    if constexpr (C::P > 1 && TRAILING_BARRIER) exchange_barrier();
 }
 
 // Global -> LDS staging -> registers.  x and dy are fetched with LDS-direct loads (the data goes
@@ -262,6 +266,7 @@ __device__ __forceinline__ void transform(float (&r)[C::E], float* lds, const Th
 // 1 KiB slot per vector, reads back exactly what it fetched, and needs no workgroup barrier --
 // only its own vmcnt (loads return in issue order) and lgkmcnt waits, which are written out here
 // because the compiler does not track the dependence between an LDS-direct load and a later LDS read.
+constexpr int kStreamPolicy = 2;   // cache-policy operand of the load: "nt" (read once, do not retain)
 typedef const __attribute__((address_space(1))) void* global_cptr;
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
@@ -272,7 +277,7 @@ __device__ __forceinline__ void stage_issue(unsigned char* wave_slot, const type
         constexpr int Cc = decltype(c)::value;
         constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V);
         __builtin_amdgcn_global_load_lds((global_cptr)(row + thread_elem + off),
-                                         (lds_ptr)(wave_slot + Cc * 1024), 16, 0, 0);
+                                         (lds_ptr)(wave_slot + Cc * 1024), 16, 0, kStreamPolicy);
     });
 }
 
@@ -427,52 +432,83 @@ __device__ __forceinline__ f32x16 hadamard_round_f32(const float* v, const Hadam
     return acc;
 }
 
+// Scheduling hints: ask the compiler to place `valu_per_mfma` vector-ALU instructions after each of
+// `count` matrix instructions, so that one tile's split runs in the shadow of the other tile's
+// (32-cycle) matrix instructions instead of after them.
+template <int COUNT, int VALU_PER_MFMA>
+__device__ __forceinline__ void interleave_mfma_with_valu() {
+#pragma unroll
+    for (int i = 0; i < COUNT; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);   // then VALU work
+    }
+}
+
 // Both rounds on every tile of the thread: bits 0..9 of the element index.
 //   from raw bfloat16 (the forward input x): round 1 needs no split
 template <class C>
 __device__ __forceinline__ void mfma_rounds_from_bf16(float (&r)[C::E], const uint4 (&raw)[C::NV],
                                                       const HadamardB& b) {
+    f32x16 d1[C::T];
     static_for<0, C::T>([&](auto tile) {
         constexpr int Tl = decltype(tile)::value;
-        const f32x16 d1 = hadamard_round_bf16(raw[2 * Tl], raw[2 * Tl + 1], b);
+        d1[Tl] = hadamard_round_bf16(raw[2 * Tl], raw[2 * Tl + 1], b);
+    });
+    static_for<0, C::T>([&](auto tile) {
+        constexpr int Tl = decltype(tile)::value;
         float v[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) v[i] = d1[i];
+        for (int i = 0; i < 16; ++i) v[i] = d1[Tl][i];
         const f32x16 d2 = hadamard_round_f32(v, b);
 #pragma unroll
         for (int i = 0; i < 16; ++i) r[16 * Tl + i] = d2[i];
     });
+    if constexpr (C::T >= 2) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * C::T, 0);        // round 1 of every tile
+        __builtin_amdgcn_sched_group_barrier(0x002, 64, 0);              // split of tile 0
+        interleave_mfma_with_valu<4 * (C::T - 1), 16>();                 // round 2 of tile t | split of t+1
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);               // round 2 of the last tile
+    }
 }
 //   from float32 registers in the first layout (the backward pass's alpha' (.) dy)
 template <class C>
 __device__ __forceinline__ void mfma_rounds_from_f32(float (&r)[C::E], const HadamardB& b) {
+    f32x16 d1[C::T];
     static_for<0, C::T>([&](auto tile) {
         constexpr int Tl = decltype(tile)::value;
-        const f32x16 d1 = hadamard_round_f32(&r[16 * Tl], b);
+        d1[Tl] = hadamard_round_f32(&r[16 * Tl], b);
+    });
+    static_for<0, C::T>([&](auto tile) {
+        constexpr int Tl = decltype(tile)::value;
         float v[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) v[i] = d1[i];
+        for (int i = 0; i < 16; ++i) v[i] = d1[Tl][i];
         const f32x16 d2 = hadamard_round_f32(v, b);
 #pragma unroll
         for (int i = 0; i < 16; ++i) r[16 * Tl + i] = d2[i];
     });
+    if constexpr (C::T >= 2) {
+        __builtin_amdgcn_sched_group_barrier(0x002, 64, 0);              // split of tile 0
+        interleave_mfma_with_valu<4 * (2 * C::T - 1), 16>();             // each round | the next split
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);               // round 2 of the last tile
+    }
 }
 
 // raw x[tok] (first layout) -> H_raw x in the last layout, whichever schedule C is.
-template <class C>
+template <class C, bool TRAILING_BARRIER>
 __device__ __forceinline__ void transform_from_raw(float (&r)[C::E], const uint4 (&raw)[C::NV],
                                                    float* lds, const ThreadMap<C>& tm,
                                                    const HadamardB& b) {
     if constexpr (C::kMfma) mfma_rounds_from_bf16<C>(r, raw, b);
     else                    unpack_all<C>(r, raw);
-    transform<C, true>(r, lds, tm);
+    transform<C, true, TRAILING_BARRIER>(r, lds, tm);
 }
 
 // registers in the last layout -> H_raw (.) in the first layout.
 template <class C>
 __device__ __forceinline__ void transform_back(float (&r)[C::E], float* lds, const ThreadMap<C>& tm,
                                                const HadamardB& b) {
-    transform<C, false>(r, lds, tm);
+    transform<C, false, false>(r, lds, tm);
     if constexpr (C::kMfma) mfma_rounds_from_f32<C>(r, b);
 }
 
@@ -543,7 +579,7 @@ __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::el
         stage_read<C>(raw, stage);
         if (more) stage_issue<C, 0>(stage, x + wk.row(grp + step) * C::D, tm.first_elem);
         float r[C::E];
-        transform_from_raw<C>(r, raw, lds, tm, hb);
+        transform_from_raw<C, true>(r, raw, lds, tm, hb);
 #pragma unroll
         for (int i = 0; i < C::E; ++i) r[i] = fmaf(r[i], a[i], b[i]);
         if (more) wait_vmem<0>();
@@ -604,7 +640,7 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
             stage_issue<C, LAST>(stage_g, dy + wk.row(grp + step) * C::D, tm.last_elem);
         }
         float r[C::E], g[C::E];
-        transform_from_raw<C>(r, raw, lds, tm, hb);           // r = H_raw x, last layout
+        transform_from_raw<C, false>(r, raw, lds, tm, hb);    // r = H_raw x, last layout
         unpack_all<C>(g, graw);
         const int64_t tok = wk.token(grp);
         const bool active = C::G == 1 || tok < N;             // one slot per workgroup: never ragged
@@ -626,6 +662,7 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
     }
 
     // Sum the G token slots of this workgroup through LDS, then write the workgroup's row.
+    if constexpr (C::G > 1) __syncthreads();      // the last exchange's reads are done everywhere
     const float s = inv_sqrt_d<C>();
     float* row = partials + (size_t)blockIdx.x * 2 * C::D;
 #pragma unroll
