@@ -22,7 +22,7 @@ static int env_int(const char* name, int fallback) {
     const char* v = getenv(name);
     if (!v || !*v) return fallback;
     const int x = atoi(v);
-    return (x >= 1 && x <= 64) ? x : fallback;
+    return (x >= 1 && x <= 256) ? x : fallback;
 }
 static int groups_per_cu(bool backward) {
     static const int fwd = env_int("WHT_AFFINE_FWD_GROUPS_PER_CU", 8);

@@ -563,16 +563,15 @@ __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::el
     if constexpr (C::kMfma) hb = make_hadamard_b();
     unsigned char* stage = stage_buf + (threadIdx.x >> 6) * (C::NV * 1024);
 
+    // first token's fetch goes out before anything else; the parameters load in its shadow
+    const int64_t step = gridDim.x;
+    int64_t grp = blockIdx.x;
+    if (grp < wk.groups) stage_issue<C, 0>(stage, x + wk.row(grp) * C::D, tm.first_elem);
+
     float a[C::E], b[C::E];
     param_get<C, LAST>(a, alpha, tm.last_elem, inv_sqrt_d<C>());
     param_get<C, LAST>(b, beta, tm.last_elem, 1.0f);
-
-    const int64_t step = gridDim.x;
-    int64_t grp = blockIdx.x;
-    if (grp < wk.groups) {
-        stage_issue<C, 0>(stage, x + wk.row(grp) * C::D, tm.first_elem);
-        wait_vmem<0>();
-    }
+    wait_vmem<0>();
     for (; grp < wk.groups; grp += step) {
         const bool more = grp + step < wk.groups;
         uint4 raw[C::NV];
@@ -618,18 +617,18 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
     unsigned char* stage_x = stage_x_buf + (threadIdx.x >> 6) * (C::NV * 1024);
     unsigned char* stage_g = stage_g_buf + (threadIdx.x >> 6) * (C::NV * 1024);
 
-    float a[C::E], da[C::E], db[C::E];
-    param_get<C, LAST>(a, alpha, tm.last_elem, inv_sqrt_d<C>());
-#pragma unroll
-    for (int i = 0; i < C::E; ++i) { da[i] = 0.0f; db[i] = 0.0f; }
-
     const int64_t step = gridDim.x;
     int64_t grp = blockIdx.x;
     if (grp < wk.groups) {
         stage_issue<C, 0>(stage_x, x + wk.row(grp) * C::D, tm.first_elem);
         stage_issue<C, LAST>(stage_g, dy + wk.row(grp) * C::D, tm.last_elem);
-        wait_vmem<0>();
     }
+
+    float a[C::E], da[C::E], db[C::E];
+    param_get<C, LAST>(a, alpha, tm.last_elem, inv_sqrt_d<C>());
+#pragma unroll
+    for (int i = 0; i < C::E; ++i) { da[i] = 0.0f; db[i] = 0.0f; }
+    wait_vmem<0>();
     for (; grp < wk.groups; grp += step) {
         const bool more = grp + step < wk.groups;
         uint4 raw[C::NV], graw[C::NV];
