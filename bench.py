@@ -212,8 +212,10 @@ def cpu_baseline(synth, w, target_seconds):
 
 
 def decode_latency(torch, wht, synth, iters=1000):
-    """Per-call time of the decode shapes (one new token per sequence, d = 4096): back-to-back
-    launches, and the same-shape dense GEMV/GEMM."""
+    """Per-call time of the decode shapes (one new token per sequence, d = 4096), two ways:
+    back-to-back calls through the Python binding (launch path included), and the same calls
+    captured once into a HIP graph and replayed (GPU-side time per call, no host launch path);
+    next to them the same-shape dense GEMV/GEMM."""
     rows = []
     for name in ("C4_decode_n1", "C4_decode_n16", "C4_decode_n64", "C4_decode_n256"):
         w = synth.WORKLOADS[name]
@@ -229,7 +231,38 @@ def decode_latency(torch, wht, synth, iters=1000):
         torch.cuda.synchronize()
         us = a.elapsed_time(e) * 1e3 / iters
         dense = dense_wo(torch, w, iters=200)
-        rows.append({"N": w.N, "d": w.d, "wht_affine_us_per_call": us, "dense_wo_us_per_call": dense["fwd_ms"] * 1e3})
+        row = {"N": w.N, "d": w.d, "wht_affine_us_per_call": us, "dense_wo_us_per_call": dense["fwd_ms"] * 1e3,
+               "wht_affine_us_per_call_graph": None, "dense_wo_us_per_call_graph": None}
+        try:
+            per_graph = 50
+            xd = torch.randn(w.N, w.d, device="cuda", dtype=torch.bfloat16)
+            Wd = torch.randn(w.d, w.d, device="cuda", dtype=torch.bfloat16) / (w.d ** 0.5)
+            bd = torch.zeros(w.d, device="cuda", dtype=torch.bfloat16)
+            for key, fn in (("wht_affine_us_per_call_graph", lambda: b.fwd(0)),
+                            ("dense_wo_us_per_call_graph", lambda: torch.addmm(bd, xd, Wd.t()))):
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    for _ in range(3):
+                        fn()
+                torch.cuda.current_stream().wait_stream(side)
+                torch.cuda.synchronize()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    for _ in range(per_graph):
+                        fn()
+                for _ in range(3):
+                    graph.replay()
+                torch.cuda.synchronize()
+                a.record()
+                for _ in range(20):
+                    graph.replay()
+                e.record()
+                torch.cuda.synchronize()
+                row[key] = a.elapsed_time(e) * 1e3 / (20 * per_graph)
+        except Exception as exc:                      # graph capture is a measurement nicety only
+            row["graph_note"] = f"graph replay not measured: {type(exc).__name__}: {exc}"[:200]
+        rows.append(row)
     return rows
 
 
