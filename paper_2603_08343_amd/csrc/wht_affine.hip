@@ -55,8 +55,12 @@ static int launch_backward(const void* dy, const void* x, const float* alpha, vo
                        static_cast<const T*>(dy), static_cast<const T*>(x), alpha, static_cast<T*>(dx),
                        static_cast<float*>(workspace), N);
     if (hipGetLastError() != hipSuccess) return WHT_ERR_LAUNCH;
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((C::D + 63) / 64, 2), dim3(1024), 0, stream,
-                       static_cast<const float*>(workspace), grid, C::D, dalpha, dbeta);
+    if constexpr (C::D >= 4096)
+        hipLaunchKernelGGL(reduce_partials_kernel<16>, dim3(C::D / 64, 2), dim3(1024), 0, stream,
+                           static_cast<const float*>(workspace), grid, C::D, dalpha, dbeta);
+    else
+        hipLaunchKernelGGL(reduce_partials_kernel<4>, dim3((C::D + 15) / 16, 2), dim3(1024), 0, stream,
+                           static_cast<const float*>(workspace), grid, C::D, dalpha, dbeta);
     return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
 }
 

@@ -689,34 +689,41 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
     }
 }
 
-// out[which][j] = sum over rows of partials[row][which][j].  Workgroup = 16 float4 columns x 64
-// row lanes: lane r adds rows r, r+64, ... in index order, then the 64 lane sums are added in lane
-// order -- a fixed association, independent of scheduling.
+// out[which][j] = sum over rows of partials[row][which][j].  Workgroup = CG float4 columns x
+// (1024 / CG) row lanes: lane r adds rows r, r + lanes, ... in index order, then the lane sums are
+// combined by a fixed binary tree -- one association, independent of scheduling, so the result is
+// bit-reproducible.  CG = 16 (256 contiguous bytes per row) for large d; CG = 4 keeps the grid wide
+// (d/16 x 2 workgroups) for small d, where this kernel is otherwise pure latency.
+template <int CG>
 __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float* __restrict__ partials,
                                                                int rows, int d,
                                                                float* __restrict__ dalpha,
                                                                float* __restrict__ dbeta) {
-    __shared__ float4 part[64][16];
-    const int cg = threadIdx.x & 15, lane_row = threadIdx.x >> 4;
-    const int col = (blockIdx.x * 16 + cg) * 4;           // first of this thread's 4 columns
+    constexpr int LANES = 1024 / CG;
+    __shared__ float4 part[LANES][CG];
+    const int cg = threadIdx.x % CG, lane_row = threadIdx.x / CG;
+    const int col = (blockIdx.x * CG + cg) * 4;           // first of this thread's 4 columns
     const int which = blockIdx.y;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     if (col < d) {
-        for (int r = lane_row; r < rows; r += 64) {
+        for (int r = lane_row; r < rows; r += LANES) {
             const float4 q = *reinterpret_cast<const float4*>(partials + ((size_t)r * 2 + which) * d + col);
             acc.x += q.x; acc.y += q.y; acc.z += q.z; acc.w += q.w;
         }
     }
     part[lane_row][cg] = acc;
     __syncthreads();
-    if (lane_row == 0 && col < d) {
-        float4 t = part[0][cg];
-        for (int r = 1; r < 64; ++r) {
-            const float4 q = part[r][cg];
-            t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+#pragma unroll
+    for (int half = LANES / 2; half >= 1; half >>= 1) {
+        if (lane_row < half) {
+            const float4 q = part[lane_row + half][cg];
+            acc.x += q.x; acc.y += q.y; acc.z += q.z; acc.w += q.w;
+            part[lane_row][cg] = acc;
         }
-        *reinterpret_cast<float4*>((which == 0 ? dalpha : dbeta) + col) = t;
+        __syncthreads();
     }
+    if (lane_row == 0 && col < d)
+        *reinterpret_cast<float4*>((which == 0 ? dalpha : dbeta) + col) = acc;
 }
 
 __global__ void zero_kernel(float* a, float* b, int d) {
