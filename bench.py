@@ -266,6 +266,41 @@ def decode_latency(torch, wht, synth, iters=1000):
     return rows
 
 
+def fused_residual(torch, wht, synth, name, steps=100, warmup=100):
+    """y = resid + alpha (.) Hx + beta in one kernel (3 N d s bytes) against the unfused pair:
+    the layer's forward followed by torch's in-place add on the residual stream (5 N d s bytes)."""
+    w = synth.WORKLOADS[name]
+    b = Bench(torch, wht, synth, name)
+    tdt = b.x[0].dtype
+    resid = [torch.randn(w.N, w.d, device="cuda").to(tdt) for _ in range(b.sets)]
+
+    def fused(i):
+        k = i % b.sets
+        wht.wht_affine_forward_residual(b.x[k], b.alpha, b.beta, resid[k], y=b.y[k])
+
+    def unfused(i):
+        k = i % b.sets
+        wht.wht_affine_forward(b.x[k], b.alpha, b.beta, y=b.y[k])
+        resid[k].add_(b.y[k])
+
+    out = {"workload": name}
+    for key, fn in (("fused", fused), ("unfused", unfused)):
+        for i in range(warmup):
+            fn(i)
+        a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(steps):
+            fn(i)
+        e.record()
+        torch.cuda.synchronize()
+        out[key + "_ms"] = a.elapsed_time(e) / steps
+    bytes_fused = 3 * w.N * w.d * io_bytes(w.dtype)
+    out["fused_GBs"] = bytes_fused / (out["fused_ms"] * 1e-3) / 1e9
+    out["fused_frac_hbm_peak"] = out["fused_GBs"] / HBM_PEAK_GBS
+    return out
+
+
 def recorded_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` on `workload` as measured with rocprofv3 counters
     (FETCH_SIZE + WRITE_SIZE, calibrated on the copy kernel) and recorded in the committed summary
@@ -342,6 +377,7 @@ def main():
             extras["workloads"].append(summarize(synth.WORKLOADS[name], s, f, bw))
             del b
             torch.cuda.empty_cache()
+        extras["fused_residual_forward"] = [fused_residual(torch, wht, synth, n) for n in ("C5_large", "C4b_roofline")]
         extras["decode"] = decode_latency(torch, wht, synth)
         extras["dense_wo_same_shape"] = dense_wo(torch, w)
         extras["dense_wo_same_shape"]["workload"] = w.name

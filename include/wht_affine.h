@@ -72,6 +72,20 @@ int wht_affine_forward(const void *x, const float *alpha, const float *beta, voi
                        int64_t N, int32_t d, int32_t dtype, void *stream);
 
 /*
+ * Forward with the attention block's residual add fused into the epilogue:
+ *     y = resid + alpha (.) (H x) + beta.
+ * (Eq. 1; the layer's output feeds the residual connection that follows the attention block, and
+ * Sec. 6 of the paper names missing operator fusion as what keeps its measured speed-ups below the
+ * operation count.)  One more [N,d] stream is read; the separate read-modify-write pass over y that
+ * a framework would otherwise run is saved.
+ *   resid  in   [N,d] dtype.   y may alias resid or x exactly.
+ * The gradient with respect to resid is dy itself, so wht_affine_backward serves this call too.
+ */
+int wht_affine_forward_residual(const void *x, const float *alpha, const float *beta,
+                                const void *resid, void *y,
+                                int64_t N, int32_t d, int32_t dtype, void *stream);
+
+/*
  * Bytes of device scratch wht_affine_backward needs for (N, d, dtype): per-workgroup partial sums
  * of dalpha and dbeta, float32.  Depends on d only through the launch shape; 0 when N = 0 or when
  * the arguments are invalid.  Needs no GPU.

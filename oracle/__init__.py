@@ -8,6 +8,7 @@ arrays into it:
 
     transform(x, method)                      -> z  = H x                        [N,d] float64
     forward(x, alpha, beta, method)           -> y  = alpha*z + beta             [N,d] float64
+    forward_residual(x, alpha, beta, resid)   -> y  = resid + alpha*z + beta     [N,d] float64
     backward(dy, x, alpha, method, ...)       -> dx, dalpha, dbeta               float64
     hadamard_matrix(d)                        -> H_raw (+-1 integers), entry by entry from the
                                                  oracle's sign rule
@@ -33,6 +34,7 @@ def _load():
         i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
         lib.wht_oracle_transform.argtypes = [vp, vp, i64, i64, i32, i32]
         lib.wht_oracle_forward.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32]
+        lib.wht_oracle_forward_residual.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32]
         lib.wht_oracle_backward.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i32, i32]
         lib.wht_oracle_butterfly_stage.argtypes = [vp, i64, i64]
         lib.wht_oracle_butterfly_stage.restype = None
@@ -135,6 +137,22 @@ def forward(x, alpha, beta, method: str = "fast") -> np.ndarray:
     y = np.empty((N, d), dtype=np.float64)
     _check(_load().wht_oracle_forward(_ptr(x), _ptr(alpha), _ptr(beta), _ptr(y), N, d, code,
                                       _METHODS[method]))
+    return y.reshape(x.shape)
+
+
+def forward_residual(x, alpha, beta, resid, method: str = "fast") -> np.ndarray:
+    """y = resid + alpha*(H x) + beta (Eq. 1 followed by the block's residual connection)."""
+    x, code = _stored(x)
+    resid, code_r = _stored(resid)
+    if code != code_r or x.shape != resid.shape:
+        raise ValueError("x and resid must have the same dtype and shape")
+    N, d = _shape2(x)
+    alpha, beta = _f64(alpha), _f64(beta)
+    if alpha.shape != (d,) or beta.shape != (d,):
+        raise ValueError("alpha and beta must have shape [d]")
+    y = np.empty((N, d), dtype=np.float64)
+    _check(_load().wht_oracle_forward_residual(_ptr(x), _ptr(alpha), _ptr(beta), _ptr(resid), _ptr(y),
+                                               N, d, code, _METHODS[method]))
     return y.reshape(x.shape)
 
 

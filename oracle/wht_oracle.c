@@ -11,7 +11,7 @@
  *
  *   H_raw[j][k] = (-1)^popcount(j AND k)            Sylvester ("natural") order: the 4x4 block
  *                                                   drawn in Fig. 1 has rows ++++ / +-+- / ++-- / +--+
- *   H           = H_raw / sqrt(d)                   "normalized ... H^T H = I"  (Sec. 4.1)
+ *   H           = H_raw / sqrt(d)                   the normalised matrix, H^T H = I (Sec. 4.1)
  *   z[n][j]     = sum_k H[j][k] x[n][k]             Y H per token; H is symmetric so Y H = (H y^T)^T
  *   y[n][j]     = alpha[j] * z[n][j] + beta[j]      Eq. 1
  *
@@ -159,6 +159,26 @@ int wht_oracle_forward(const void *x, const double *alpha, const double *beta, d
     for (int64_t n = 0; n < N; ++n)
         for (int64_t j = 0; j < d; ++j)
             y[n * d + j] = alpha[j] * y[n * d + j] + beta[j];
+    return 0;
+}
+
+/*
+ * Eq. 1 followed by the residual connection of the attention block (the paper's motivation for
+ * the output projection notes that its result feeds the residual add after the block; Sec. 6 names
+ * missing operator fusion as the reason the measured speed-ups lag the operation count):
+ *     y = resid + alpha (.) (H x) + beta.     resid: [N,d] of `dtype`.
+ */
+int wht_oracle_forward_residual(const void *x, const double *alpha, const double *beta,
+                                const void *resid, double *y,
+                                int64_t N, int64_t d, int dtype, int method)
+{
+    if (!resid) return -1;
+    int rc = wht_oracle_forward(x, alpha, beta, y, N, d, dtype, method);
+    if (rc) return rc;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t j = 0; j < d; ++j)
+            y[n * d + j] = widen(resid, n * d + j, dtype) + y[n * d + j];
     return 0;
 }
 

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     wht_affine_backward_workspace_bytes,
     wht_affine_copy_baseline,
     wht_affine_forward,
+    wht_affine_forward_residual,
     wht_affine_status_string,
     wht_affine_version,
 )

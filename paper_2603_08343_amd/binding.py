@@ -17,6 +17,7 @@ _lib = None
 
 EXPORTS = (
     "wht_affine_forward",
+    "wht_affine_forward_residual",
     "wht_affine_backward_workspace_bytes",
     "wht_affine_backward",
     "wht_affine_copy_baseline",
@@ -47,6 +48,8 @@ def library():
         vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
         lib.wht_affine_forward.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp]
         lib.wht_affine_forward.restype = ctypes.c_int
+        lib.wht_affine_forward_residual.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, vp]
+        lib.wht_affine_forward_residual.restype = ctypes.c_int
         lib.wht_affine_backward_workspace_bytes.argtypes = [i64, i32, i32]
         lib.wht_affine_backward_workspace_bytes.restype = sz
         lib.wht_affine_backward.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, vp, sz, vp]
@@ -65,6 +68,10 @@ def library():
 
 def wht_affine_forward_raw(x, alpha, beta, y, N, d, dtype, stream=0) -> int:
     return library().wht_affine_forward(x, alpha, beta, y, N, d, dtype, stream)
+
+
+def wht_affine_forward_residual_raw(x, alpha, beta, resid, y, N, d, dtype, stream=0) -> int:
+    return library().wht_affine_forward_residual(x, alpha, beta, resid, y, N, d, dtype, stream)
 
 
 def wht_affine_backward_raw(dy, x, alpha, dx, dalpha, dbeta, N, d, dtype, workspace, workspace_bytes,
@@ -138,6 +145,27 @@ def wht_affine_forward(x, alpha, beta, y=None, stream=None):
                                     _dtype_code(x, torch), _stream_handle(stream, torch, x.device))
     if rc != 0:
         raise WhtAffineError(rc, "wht_affine_forward")
+    return y
+
+
+def wht_affine_forward_residual(x, alpha, beta, resid, y=None, stream=None):
+    """y = resid + alpha (.) (H x) + beta: the layer with the block's residual add fused in."""
+    torch = _torch()
+    _check_io(x, "x", torch)
+    _check_io(resid, "resid", torch, like=x)
+    N, d = x.shape
+    _check_param(alpha, "alpha", d, x, torch)
+    _check_param(beta, "beta", d, x, torch)
+    if y is None:
+        y = torch.empty_like(x)
+    else:
+        _check_io(y, "y", torch, like=x)
+    ptrs = (x.data_ptr(), resid.data_ptr(), y.data_ptr()) if N > 0 else (alpha.data_ptr(),) * 3
+    with torch.cuda.device(x.device):
+        rc = wht_affine_forward_residual_raw(ptrs[0], alpha.data_ptr(), beta.data_ptr(), ptrs[1], ptrs[2], N, d,
+                                             _dtype_code(x, torch), _stream_handle(stream, torch, x.device))
+    if rc != 0:
+        raise WhtAffineError(rc, "wht_affine_forward_residual")
     return y
 
 

@@ -38,11 +38,17 @@ static int grid_for(int64_t N, bool backward) {
 }
 
 template <class C>
-static int launch_forward(const void* x, const float* alpha, const float* beta, void* y, int64_t N,
-                          hipStream_t stream) {
+static int launch_forward(const void* x, const float* alpha, const float* beta, const void* resid, void* y,
+                          int64_t N, hipStream_t stream) {
     using T = typename C::io::elem_t;
-    hipLaunchKernelGGL(forward_kernel<C>, dim3(grid_for<C>(N, false)), dim3(C::BT), 0, stream,
-                       static_cast<const T*>(x), alpha, beta, static_cast<T*>(y), N);
+    if (resid)
+        hipLaunchKernelGGL((forward_kernel<C, true>), dim3(grid_for<C>(N, false)), dim3(C::BT), 0, stream,
+                           static_cast<const T*>(x), alpha, beta, static_cast<const T*>(resid),
+                           static_cast<T*>(y), N);
+    else
+        hipLaunchKernelGGL((forward_kernel<C, false>), dim3(grid_for<C>(N, false)), dim3(C::BT), 0, stream,
+                           static_cast<const T*>(x), alpha, beta, static_cast<const T*>(nullptr),
+                           static_cast<T*>(y), N);
     return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
 }
 
@@ -70,7 +76,7 @@ static size_t workspace_for(int64_t N) { return (size_t)grid_for<C>(N, true) * 2
 enum class Op { Forward, Backward, Workspace };
 
 struct Args {
-    const void* x; const void* dy; const float* alpha; const float* beta;
+    const void* x; const void* dy; const void* resid; const float* alpha; const float* beta;
     void* y; void* dx; float* dalpha; float* dbeta;
     int64_t N; void* workspace; hipStream_t stream;
     size_t workspace_out;
@@ -79,7 +85,7 @@ struct Args {
 template <class C>
 static int run(Op op, Args& a) {
     switch (op) {
-    case Op::Forward:  return launch_forward<C>(a.x, a.alpha, a.beta, a.y, a.N, a.stream);
+    case Op::Forward:  return launch_forward<C>(a.x, a.alpha, a.beta, a.resid, a.y, a.N, a.stream);
     case Op::Backward: return launch_backward<C>(a.dy, a.x, a.alpha, a.dx, a.dalpha, a.dbeta, a.N,
                                                  a.workspace, a.stream);
     default:           a.workspace_out = workspace_for<C>(a.N); return WHT_OK;
@@ -151,18 +157,30 @@ static int check_dims(int64_t N, int32_t d, int32_t dtype, int* logd) {
 
 extern "C" {
 
-int wht_affine_forward(const void* x, const float* alpha, const float* beta, void* y, int64_t N,
-                       int32_t d, int32_t dtype, void* stream) {
+static int forward_common(const void* x, const float* alpha, const float* beta, const void* resid,
+                          bool with_resid, void* y, int64_t N, int32_t d, int32_t dtype, void* stream) {
     using namespace wht;
-    if (!x || !alpha || !beta || !y) return WHT_ERR_NULL_PTR;
+    if (!x || !alpha || !beta || !y || (with_resid && !resid)) return WHT_ERR_NULL_PTR;
     int logd = 0;
     if (int rc = check_dims(N, d, dtype, &logd)) return rc;
-    if (!aligned16(x) || !aligned16(y) || !aligned16(alpha) || !aligned16(beta)) return WHT_ERR_MISALIGNED;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(alpha) || !aligned16(beta) ||
+        (with_resid && !aligned16(resid)))
+        return WHT_ERR_MISALIGNED;
     if (N == 0) return WHT_OK;
     Args a{};
-    a.x = x; a.alpha = alpha; a.beta = beta; a.y = y; a.N = N;
+    a.x = x; a.alpha = alpha; a.beta = beta; a.resid = with_resid ? resid : nullptr; a.y = y; a.N = N;
     a.stream = static_cast<hipStream_t>(stream);
     return dispatch(logd, dtype, Op::Forward, a);
+}
+
+int wht_affine_forward(const void* x, const float* alpha, const float* beta, void* y, int64_t N,
+                       int32_t d, int32_t dtype, void* stream) {
+    return forward_common(x, alpha, beta, nullptr, false, y, N, d, dtype, stream);
+}
+
+int wht_affine_forward_residual(const void* x, const float* alpha, const float* beta, const void* resid,
+                                void* y, int64_t N, int32_t d, int32_t dtype, void* stream) {
+    return forward_common(x, alpha, beta, resid, true, y, N, d, dtype, stream);
 }
 
 size_t wht_affine_backward_workspace_bytes(int64_t N, int32_t d, int32_t dtype) {
@@ -207,7 +225,7 @@ int wht_affine_copy_baseline(const void* src, void* dst, size_t bytes, void* str
     if (bytes == 0) return WHT_OK;
     const size_t nvec = bytes / 16;
     const size_t want = (nvec + 1023) / 1024;
-    const int grid = (int)(want < (size_t)kNumCU * 8 ? want : (size_t)kNumCU * 8);
+    const int grid = (int)(want < (size_t)kNumCU * 64 ? want : (size_t)kNumCU * 64);
     hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const uint4*>(src), static_cast<uint4*>(dst), nvec);
     return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;

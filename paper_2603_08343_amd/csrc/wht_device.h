@@ -535,25 +535,29 @@ struct Walker {
     }
 };
 
-// forward:  y = (alpha / sqrt d) (.) (H_raw x) + beta
+// forward:  y = (alpha / sqrt d) (.) (H_raw x) + beta      [+ resid when RESID]
 //
-// Per iteration k (x(k) has landed in its stage):
+// Per iteration k (x(k) [and resid(k)] have landed in their stages):
 //   raw <- stage;  issue x(k+1) -> stage;  transform raw;  affine;  wait for everything pending;
 //   store y(k).
 // The one wait sits just before the stores of y(k): all it can be waiting for is x(k+1), issued a
 // whole transform earlier, and the stores of y(k-1), a whole iteration old.  (Loads and stores may
 // complete out of order with respect to each other, so a counted wait is only safe when nothing
 // but older loads is pending; waiting here, before the new stores, keeps it that way.)
-template <class C>
+// RESID fuses the attention block's residual add into the epilogue: resid is one more staged
+// stream, fetched in the layout y is stored in.
+template <class C, bool RESID>
 __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::elem_t* x,
                                                         const float* __restrict__ alpha,
                                                         const float* __restrict__ beta,
+                                                        const typename C::io::elem_t* resid,
                                                         typename C::io::elem_t* y,
                                                         int64_t N) {
     // separate LDS objects: the compiler can then tell that the exchange region's accesses never
     // alias an LDS-direct load in flight, and does not wait for the prefetch before them
     __shared__ __align__(16) float lds[C::kExchangeBytes / 4];
     __shared__ __align__(16) unsigned char stage_buf[C::kStageBytes];
+    __shared__ __align__(16) unsigned char stage_r_buf[RESID ? C::kStageBytes : 16];
     constexpr int LAST = C::P - 1;
     const unsigned t = threadIdx.x % C::TPT;
     Walker<C> wk{N, (N + C::G - 1) / C::G, threadIdx.x / C::TPT};
@@ -562,11 +566,15 @@ __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::el
     HadamardB hb{};
     if constexpr (C::kMfma) hb = make_hadamard_b();
     unsigned char* stage = stage_buf + (threadIdx.x >> 6) * (C::NV * 1024);
+    unsigned char* stage_r = stage_r_buf + (RESID ? (threadIdx.x >> 6) * (C::NV * 1024) : 0);
 
     // first token's fetch goes out before anything else; the parameters load in its shadow
     const int64_t step = gridDim.x;
     int64_t grp = blockIdx.x;
-    if (grp < wk.groups) stage_issue<C, 0>(stage, x + wk.row(grp) * C::D, tm.first_elem);
+    if (grp < wk.groups) {
+        stage_issue<C, 0>(stage, x + wk.row(grp) * C::D, tm.first_elem);
+        if constexpr (RESID) stage_issue<C, LAST>(stage_r, resid + wk.row(grp) * C::D, tm.last_elem);
+    }
 
     float a[C::E], b[C::E];
     param_get<C, LAST>(a, alpha, tm.last_elem, inv_sqrt_d<C>());
@@ -574,13 +582,24 @@ __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::el
     wait_vmem<0>();
     for (; grp < wk.groups; grp += step) {
         const bool more = grp + step < wk.groups;
-        uint4 raw[C::NV];
+        uint4 raw[C::NV], rraw[RESID ? C::NV : 1];
         stage_read<C>(raw, stage);
-        if (more) stage_issue<C, 0>(stage, x + wk.row(grp + step) * C::D, tm.first_elem);
+        if constexpr (RESID) stage_read<C>(rraw, stage_r);
+        if (more) {
+            stage_issue<C, 0>(stage, x + wk.row(grp + step) * C::D, tm.first_elem);
+            if constexpr (RESID) stage_issue<C, LAST>(stage_r, resid + wk.row(grp + step) * C::D, tm.last_elem);
+        }
         float r[C::E];
         transform_from_raw<C, true>(r, raw, lds, tm, hb);
+        if constexpr (RESID) {
+            float res[C::E];
+            unpack_all<C>(res, rraw);
 #pragma unroll
-        for (int i = 0; i < C::E; ++i) r[i] = fmaf(r[i], a[i], b[i]);
+            for (int i = 0; i < C::E; ++i) r[i] = res[i] + fmaf(r[i], a[i], b[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < C::E; ++i) r[i] = fmaf(r[i], a[i], b[i]);
+        }
         if (more) wait_vmem<0>();
         const int64_t tok = wk.token(grp);
         global_put<C, LAST>(r, y + tok * C::D, tm.last_elem, tok < N);
@@ -733,17 +752,17 @@ __global__ void zero_kernel(float* a, float* b, int d) {
 
 __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
                                                    size_t nvec) {
+    // same policy as the layer's kernels: 16 bytes per lane, non-temporal both ways
     const size_t stride = (size_t)gridDim.x * blockDim.x * 4;
     for (size_t base = ((size_t)blockIdx.x * blockDim.x) * 4 + threadIdx.x; base < nvec; base += stride) {
         uint4 v[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            if (base + k * 256 < nvec) v[k] = src[base + k * 256];
+            if (base + k * 256 < nvec) v[k] = stream_load16(src + base + k * 256);
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            if (base + k * 256 < nvec) dst[base + k * 256] = v[k];
+            if (base + k * 256 < nvec) stream_store16(dst + base + k * 256, v[k]);
     }
 }
-
 
 }  // namespace wht

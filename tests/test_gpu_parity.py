@@ -96,6 +96,41 @@ def test_many_passes_per_workgroup():
     check_backward_full(inp2, "bwd strided d=64")
 
 
+# ------------------------------------------------------------------ residual add fused into the epilogue
+
+@pytest.mark.parametrize("d,dtype,N", [(64, "f32", 70), (256, "f32", 64), (512, "bf16", 131), (1024, "bf16", 263),
+                                       (2048, "bf16", 67), (4096, "bf16", 35), (8192, "bf16", 1031),
+                                       (16384, "bf16", 5), (8192, "f32", 9)])
+def test_forward_residual(d, dtype, N):
+    _announce(f"forward+residual d={d} {dtype} N={N}")
+    inp = synth.make_inputs(N, d, dtype, seed=d + 7)          # dy doubles as the residual stream
+    x, resid = to_gpu(inp.x, dtype), to_gpu(inp.dy, dtype)
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    y = wht.wht_affine_forward_residual(x, a, b, resid)
+    torch.cuda.synchronize()
+    ref = oracle.forward_residual(inp.x, inp.alpha, inp.beta, inp.dy, _method(d))
+    assert_io_close(y, ref, dtype, f"fwd+resid d={d} {dtype}")
+    # in place on the residual stream, as a framework would call it
+    wht.wht_affine_forward_residual(x, a, b, resid, y=resid)
+    torch.cuda.synchronize()
+    assert torch.equal(resid.view(torch.int16 if dtype == "bf16" else torch.int32),
+                       y.view(torch.int16 if dtype == "bf16" else torch.int32))
+
+
+def test_forward_residual_full_size_C5():
+    w = synth.WORKLOADS["C5_large"]
+    _announce("forward+residual at C5 size (sampled tokens)")
+    inp = synth.make_workload("C5_large")
+    idx = _sample_tokens(w.N, 32, seed=5)
+    x, resid = to_gpu(inp.x, "bf16"), to_gpu(inp.dy, "bf16")
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    y = wht.wht_affine_forward_residual(x, a, b, resid)
+    torch.cuda.synchronize()
+    ref = oracle.forward_residual(inp.x[idx], inp.alpha, inp.beta, inp.dy[idx], "fast")
+    assert_io_close(y[torch.from_numpy(idx).cuda()], ref, "bf16", "C5 fwd+resid (sampled tokens)")
+    assert torch.all(torch.isfinite(y.float()))
+
+
 # ------------------------------------------------------------------ the benchmark configurations
 
 def test_config_C1_tiny():

@@ -63,6 +63,15 @@ def test_forward_argument_validation(args, want):
     assert binding.wht_affine_forward_raw(*args) == want
 
 
+def test_forward_residual_argument_validation():
+    call = binding.wht_affine_forward_residual_raw
+    assert call(P, P, P, 0, P, 4, 256, 1) == NULLP            # resid is required here
+    assert call(P, P, P, P + 8, P, 4, 256, 1) == ALIGN
+    assert call(P, P, P, P, P, 4, 768, 1) == DIM
+    assert call(P, P, P, P, P, 4, 256, 3) == DTYPE
+    assert call(P, P, P, P, P, 0, 256, 1) == OK
+
+
 def test_backward_argument_validation():
     ws = binding.wht_affine_backward_workspace_bytes(100, 1024, 1)
     assert ws > 0 and ws % 16 == 0

@@ -181,6 +181,27 @@ def test_affine_special_cases(method):
     assert np.allclose(oracle.forward(e, alpha, beta, method), alpha * col + beta, atol=1e-15)
 
 
+def test_forward_residual_special_cases():
+    d = 32
+    x, resid = RNG.standard_normal((5, d)), RNG.standard_normal((5, d))
+    alpha, beta = RNG.uniform(0.5, 1.5, d), 0.02 * RNG.standard_normal(d)
+    for method in ("matrix", "fast"):
+        # zero residual: the plain layer; zero input: residual + beta; hand-worked d = 4
+        assert np.array_equal(oracle.forward_residual(x, alpha, beta, np.zeros((5, d)), method),
+                              oracle.forward(x, alpha, beta, method))
+        assert np.allclose(oracle.forward_residual(np.zeros((5, d)), alpha, beta, resid, method), resid + beta,
+                           rtol=0, atol=1e-15)
+        y = oracle.forward_residual(np.array([[1.0, 2.0, 3.0, 4.0]]), np.array([1.0, 2.0, 3.0, 4.0]),
+                                    np.full(4, 0.5), np.array([[10.0, 20.0, 30.0, 40.0]]), method)
+        assert np.array_equal(y, [[15.5, 18.5, 24.5, 40.5]])
+        # the gradient with respect to the residual is the identity: finite difference of sum(w*y)
+        w = RNG.standard_normal((5, d))
+        base = np.sum(w * oracle.forward_residual(x, alpha, beta, resid, method))
+        bumped = resid.copy()
+        bumped[2, 7] += 1e-3
+        assert abs((np.sum(w * oracle.forward_residual(x, alpha, beta, bumped, method)) - base) / 1e-3 - w[2, 7]) < 1e-9
+
+
 # ---------------------------------------------------------------- stored dtypes are widened exactly
 
 def test_bf16_and_f32_inputs_widen_exactly():
