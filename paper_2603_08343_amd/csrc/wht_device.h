@@ -432,19 +432,9 @@ __device__ __forceinline__ f32x16 hadamard_round_f32(const float* v, const Hadam
     return acc;
 }
 
-// Scheduling hints: ask the compiler to place `valu_per_mfma` vector-ALU instructions after each of
-// `count` matrix instructions, so that one tile's split runs in the shadow of the other tile's
-// (32-cycle) matrix instructions instead of after them.
-template <int COUNT, int VALU_PER_MFMA>
-__device__ __forceinline__ void interleave_mfma_with_valu() {
-#pragma unroll
-    for (int i = 0; i < COUNT; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // one MFMA
-        __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);   // then VALU work
-    }
-}
-
-// Both rounds on every tile of the thread: bits 0..9 of the element index.
+// Both rounds on every tile of the thread: bits 0..9 of the element index.  Round 1 of every tile
+// is issued before any round 2, so that one tile's split has the other tile's matrix instructions
+// to overlap with.  (Explicit MFMA/VALU interleave hints on top of this measured no gain.)
 //   from raw bfloat16 (the forward input x): round 1 needs no split
 template <class C>
 __device__ __forceinline__ void mfma_rounds_from_bf16(float (&r)[C::E], const uint4 (&raw)[C::NV],
@@ -463,12 +453,6 @@ __device__ __forceinline__ void mfma_rounds_from_bf16(float (&r)[C::E], const ui
 #pragma unroll
         for (int i = 0; i < 16; ++i) r[16 * Tl + i] = d2[i];
     });
-    if constexpr (C::T >= 2) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2 * C::T, 0);        // round 1 of every tile
-        __builtin_amdgcn_sched_group_barrier(0x002, 64, 0);              // split of tile 0
-        interleave_mfma_with_valu<4 * (C::T - 1), 16>();                 // round 2 of tile t | split of t+1
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);               // round 2 of the last tile
-    }
 }
 //   from float32 registers in the first layout (the backward pass's alpha' (.) dy)
 template <class C>
@@ -487,11 +471,6 @@ __device__ __forceinline__ void mfma_rounds_from_f32(float (&r)[C::E], const Had
 #pragma unroll
         for (int i = 0; i < 16; ++i) r[16 * Tl + i] = d2[i];
     });
-    if constexpr (C::T >= 2) {
-        __builtin_amdgcn_sched_group_barrier(0x002, 64, 0);              // split of tile 0
-        interleave_mfma_with_valu<4 * (2 * C::T - 1), 16>();             // each round | the next split
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);               // round 2 of the last tile
-    }
 }
 
 // raw x[tok] (first layout) -> H_raw x in the last layout, whichever schedule C is.
