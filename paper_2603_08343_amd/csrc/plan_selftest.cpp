@@ -21,7 +21,8 @@
 using namespace wht;
 
 typedef unsigned (*PhysFn)(unsigned);
-static unsigned phys_skew(unsigned i) { return lds_phys(i); }
+static unsigned phys_pad2(unsigned i) { return lds_phys_pad(i, 2); }
+static unsigned phys_pad3(unsigned i) { return lds_phys_pad(i, 3); }
 static unsigned phys_rot(unsigned i) { return lds_phys_rot(i); }
 
 static unsigned thread_elem(const PhaseDesc& p, int n, int e, unsigned t) {
@@ -155,7 +156,7 @@ int main(int argc, char** argv) {
     for (int v : {2, 3})
         for (int n = 5; n <= (v == 2 ? 13 : 14); ++n) {
             const PlanDesc pl = make_plan(n, log_e_for(n, v), v);
-            ok = check("butterfly", pl, phys_skew, lds_words_skew(1u << n), verbose) && ok;
+            ok = check("butterfly", pl, v == 2 ? phys_pad2 : phys_pad3, lds_words_pad(1u << n, v), verbose) && ok;
         }
     for (int n = 10; n <= 14; ++n) {
         const PlanDesc pl = make_mfma_plan(n, mfma_log_tiles(n));

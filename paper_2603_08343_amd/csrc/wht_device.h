@@ -99,8 +99,8 @@ struct Cfg {
     static constexpr int TPT = 1 << (n - e);    // threads per token
     static constexpr int BT = TPT > 256 ? TPT : 256;   // threads per workgroup
     static constexpr int G = BT / TPT;          // tokens per workgroup pass
-    static constexpr unsigned phys(unsigned i) { return lds_phys(i); }
-    static constexpr unsigned kTokenWords = lds_words_skew(D);
+    static constexpr unsigned phys(unsigned i) { return lds_phys_pad(i, v); }
+    static constexpr unsigned kTokenWords = lds_words_pad(D, v);
     static constexpr unsigned kExchangeBytes = (P > 1 || G > 1) ? G * kTokenWords * 4u : 16u;
     static constexpr unsigned kStageBytes = BT * NV * 16u;          // one tensor's token group, as stored
     static constexpr unsigned kLdsBytes = kExchangeBytes + kStageBytes;              // forward

@@ -182,11 +182,21 @@ constexpr int mfma_log_tiles(int logd) { return logd <= 10 ? 0 : (logd <= 13 ? 1
 // Both are linear in the bits of i (phys(a | b) = phys(a) + phys(b) for disjoint a, b) and keep four
 // consecutive elements in one aligned 16-byte group.
 
-// Butterfly schedule: +4 words every 64 elements keeps the 16-byte-per-lane accesses of the
-// first/last layouts off each other's banks, +8 words every 256 elements does the same for the
-// one-word accesses of the middle layouts (lanes 256 elements apart).
-constexpr unsigned lds_phys(unsigned i) { return i + ((i >> 6) << 2) + ((i >> 8) << 3); }
-constexpr unsigned lds_words_skew(unsigned d) { return (lds_phys(d - 1) + 1 + 3) & ~3u; }
+// Butterfly schedule, padded maps.  The LDS has 32 banks of 4 bytes.
+//   8-element vectors (bfloat16 I/O): +4 words every 64 elements keeps the 16-byte-per-lane accesses
+//   of the first/last layouts (lane stride 8 words) off each other's banks, +8 words every 256
+//   elements does the same for the one-word accesses of the middle layouts (9.4 % of LDS).
+//   4-element vectors (fp32 I/O): +4 words every 32 elements and +4 more every 128 elements; the
+//   middle layouts' one-word accesses (lanes 2^7 .. 2^10 elements apart) then spread over all banks.
+//   Measured at d = 8192: fp32 backward 4 % faster than with the map above; with bfloat16 I/O the
+//   bank-conflict cycle counter falls to a third, but the map costs 15.6 % of LDS, which there drops
+//   a CU from three resident workgroups to two (forward 12 % slower), so the 8-element case keeps
+//   the smaller map.
+constexpr unsigned lds_phys_pad(unsigned i, int v) {
+    return v == 3 ? i + ((i >> 6) << 2) + ((i >> 8) << 3)
+                  : i + ((i >> 5) << 2) + ((i >> 7) << 2);
+}
+constexpr unsigned lds_words_pad(unsigned d, int v) { return (lds_phys_pad(d - 1, v) + 1 + 3) & ~3u; }
 
 // Matrix-core schedule: both layouts give lane l the 8 elements starting at 8*l (+ multiples of
 // 512) as two 16-byte accesses.  Moving element bit 2 above the six lane bits makes each of those
