@@ -12,10 +12,12 @@ arrays into it:
     backward(dy, x, alpha, method, ...)       -> dx, dalpha, dbeta               float64
     hadamard_matrix(d)                        -> H_raw (+-1 integers), entry by entry from the
                                                  oracle's sign rule
+    h12()                                     -> the order-12 factor used for d = 12 * 2^m
     butterfly_stage(a, stride)                -> one stage of the Fig. 2 network
 
 `x`/`dy` may be float64, float32, or uint16 arrays holding bfloat16 bit patterns (widened exactly).
-method: "matrix" = the O(d^2) definition, "fast" = the butterfly network.  Every public function
+method: "matrix" = the O(d^2) definition, "fast" = the butterfly network.  d is 2^n, or 12 * 2^m (this library's reading of the widths
+768 and 1536 of Table 2: H = P12 (x) Sylvester, see wht_oracle.c).  Every public function
 here is pinned by tests/test_oracle_pins.py (no function is "parity unpinned").
 """
 import ctypes
@@ -39,6 +41,8 @@ def _load():
         lib.wht_oracle_butterfly_stage.argtypes = [vp, i64, i64]
         lib.wht_oracle_butterfly_stage.restype = None
         lib.wht_oracle_sign.argtypes = [ctypes.c_uint32, ctypes.c_uint32]
+        lib.wht_oracle_sign_d.argtypes = [i64, ctypes.c_uint32, ctypes.c_uint32]
+        lib.wht_oracle_h12.argtypes = [i32, i32]
         lib.wht_oracle_bf16_bits_to_double.argtypes = [ctypes.c_uint16]
         lib.wht_oracle_bf16_bits_to_double.restype = ctypes.c_double
         lib.wht_oracle_set_num_threads.argtypes = [i32]
@@ -77,7 +81,7 @@ def _shape2(a):
 
 def _check(rc):
     if rc != 0:
-        raise ValueError(f"oracle rejected its arguments (rc={rc}): d must be a power of two")
+        raise ValueError(f"oracle rejected its arguments (rc={rc}): d must be 2^n or 12 * 2^m")
 
 
 def num_threads() -> int:
@@ -94,11 +98,20 @@ def sign(j: int, k: int) -> int:
 
 def hadamard_matrix(d: int) -> np.ndarray:
     """Unnormalised d x d sign matrix, built entry by entry from the oracle's sign rule."""
+    lib = _load()
     H = np.empty((d, d), dtype=np.int64)
     for j in range(d):
         for k in range(d):
-            H[j, k] = sign(j, k)
+            H[j, k] = lib.wht_oracle_sign_d(d, j, k)
+    if (H == 0).any():
+        raise ValueError("d must be 2^n or 12 * 2^m")
     return H
+
+
+def h12() -> np.ndarray:
+    """The symmetric, normalised order-12 Hadamard matrix used for d = 12 * 2^m."""
+    lib = _load()
+    return np.array([[lib.wht_oracle_h12(a, b) for b in range(12)] for a in range(12)], dtype=np.int64)
 
 
 def bf16_bits_to_float64(bits) -> np.ndarray:

@@ -22,11 +22,27 @@
  *   dalpha[j] = sum_n dy[n][j] * z[n][j]
  *   dx[n][k]  = sum_j H[j][k] * alpha[j] * dy[n][j]
  *
+ * Widths d = 12 * 2^m (the paper trains d = 768 and d = 1536, Table 2, and does not say which
+ * matrix it uses there; this is this library's reading):
+ *
+ *   H_raw = P12 (x) S_{2^m}                         Kronecker product: S is the Sylvester matrix above,
+ *                                                   P12 acts across the 12 contiguous blocks of 2^m
+ *                                                   features, H_raw[j][k] = P12[j / 2^m][k / 2^m] *
+ *                                                   (-1)^popcount((j mod 2^m) AND (k mod 2^m))
+ *   P12                                             the symmetric order-12 Hadamard matrix of Paley's
+ *                                                   second construction over GF(5), with rows and
+ *                                                   columns negated so that row 0 and column 0 are all +1
+ *
+ * P12 is symmetric with +-1 entries and P12 P12 = 12 I, so everything Sec. 4.1 uses still holds:
+ * H = H_raw / sqrt(d) is symmetric, orthogonal, has entries +-1/sqrt(d) and a constant first row.
+ *
  * Two independent ways to apply H are provided and cross-checked by the tests:
  *   method 0  "matrix": the definition, an explicit O(d^2) sum per token;
  *   method 1  "fast"  : the in-place butterfly network of Fig. 2 -- stages with stride
  *                       1, 2, 4, ..., d/2; each stage replaces the pair (a_i, a_{i+stride}) by
  *                       (a_i + a_{i+stride}, a_i - a_{i+stride}) -- followed by one 1/sqrt(d) scale.
+ *                       For d = 12 * 2^m the strides stop at 2^(m-1) (each block of 2^m on its own)
+ *                       and the 12 blocks are then combined entry by entry with P12.
  *
  * All arithmetic is IEEE double.  Inputs may be stored as double, float or bfloat16 bit patterns;
  * they are widened exactly, so input rounding is never part of an error budget.
@@ -66,6 +82,13 @@ static double widen(const void *base, int64_t idx, int dtype)
 
 static int is_pow2(int64_t d) { return d >= 1 && (d & (d - 1)) == 0; }
 
+/* Widths with a definition here: 2^n, and 12 * 2^m. */
+static int is_twelve_width(int64_t d) { return d >= 12 && d % 12 == 0 && is_pow2(d / 12); }
+static int is_width(int64_t d) { return is_pow2(d) || is_twelve_width(d); }
+
+/* Length of the Sylvester factor: d itself, or 2^m for d = 12 * 2^m. */
+static int64_t sylvester_len(int64_t d) { return is_pow2(d) ? d : d / 12; }
+
 /* ---- the sign pattern (Fig. 1) -------------------------------------------------------------- */
 
 /* +1 or -1: entry (j,k) of the unnormalised Sylvester Hadamard matrix. */
@@ -77,6 +100,51 @@ int wht_oracle_sign(uint32_t j, uint32_t k)
     return (ones % 2 == 0) ? 1 : -1;
 }
 
+/* ---- the order-12 factor ---------------------------------------------------------------------- */
+
+/* Quadratic character of GF(5): 0 for 0, +1 for the squares {1, 4}, -1 for {2, 3}. */
+static int chi5(int a)
+{
+    a %= 5;
+    if (a < 0) a += 5;
+    if (a == 0) return 0;
+    return (a == 1 || a == 4) ? 1 : -1;
+}
+
+/* Symmetric conference matrix of order 6: zero diagonal, first row and column +1, Jacobsthal core. */
+static int conference6(int i, int j)
+{
+    if (i == j) return 0;
+    if (i == 0 || j == 0) return 1;
+    return chi5(i - j);
+}
+
+/* Paley's second construction: every entry c of the conference matrix becomes c * [[1,1],[1,-1]],
+ * every zero (the diagonal) becomes [[1,-1],[-1,-1]]. */
+static int paley12_raw(int a, int b)
+{
+    static const int plus_block[2][2]  = { { 1, 1 }, { 1, -1 } };
+    static const int diag_block[2][2]  = { { 1, -1 }, { -1, -1 } };
+    int i = a / 2, u = a % 2, j = b / 2, v = b % 2;
+    return (i == j) ? diag_block[u][v] : conference6(i, j) * plus_block[u][v];
+}
+
+/* Entry (a,b), 0 <= a,b < 12, of P12: row a and column b of the raw matrix are negated when the raw
+ * matrix has -1 in row 0 at that index, which makes row 0 and column 0 all +1 and keeps symmetry. */
+int wht_oracle_h12(int a, int b)
+{
+    return paley12_raw(0, a) * paley12_raw(a, b) * paley12_raw(0, b);
+}
+
+/* +1 or -1: entry (j,k) of the unnormalised matrix of width d (d = 2^n or 12 * 2^m; 0 otherwise). */
+int wht_oracle_sign_d(int64_t d, uint32_t j, uint32_t k)
+{
+    if (!is_width(d) || j >= d || k >= d) return 0;
+    if (is_pow2(d)) return wht_oracle_sign(j, k);
+    uint32_t len = (uint32_t)sylvester_len(d);
+    return wht_oracle_h12((int)(j / len), (int)(k / len)) * wht_oracle_sign(j % len, k % len);
+}
+
 /* ---- method 0: the definition --------------------------------------------------------------- */
 
 /* out[j] = (1/sqrt d) sum_k sign(j,k) in[k] */
@@ -86,7 +154,7 @@ static void apply_H_matrix(const double *in, double *out, int64_t d)
     for (int64_t j = 0; j < d; ++j) {
         double acc = 0.0;
         for (int64_t k = 0; k < d; ++k)
-            acc += (double)wht_oracle_sign((uint32_t)j, (uint32_t)k) * in[k];
+            acc += (double)wht_oracle_sign_d(d, (uint32_t)j, (uint32_t)k) * in[k];
         out[j] = scale * acc;
     }
 }
@@ -109,9 +177,21 @@ void wht_oracle_butterfly_stage(double *a, int64_t d, int64_t stride)
 static void apply_H_fast(const double *in, double *out, int64_t d)
 {
     const double scale = 1.0 / sqrt((double)d);
+    const int64_t len = sylvester_len(d);
     for (int64_t k = 0; k < d; ++k) out[k] = in[k];
-    for (int64_t stride = 1; stride < d; stride *= 2)
+    for (int64_t stride = 1; stride < len; stride *= 2)
         wht_oracle_butterfly_stage(out, d, stride);
+    if (len != d) {                              /* d = 12 * len: combine the 12 blocks with P12 */
+        for (int64_t r = 0; r < len; ++r) {
+            double blk[12];
+            for (int b = 0; b < 12; ++b) blk[b] = out[b * len + r];
+            for (int a = 0; a < 12; ++a) {
+                double acc = 0.0;
+                for (int b = 0; b < 12; ++b) acc += (double)wht_oracle_h12(a, b) * blk[b];
+                out[a * len + r] = acc;
+            }
+        }
+    }
     for (int64_t k = 0; k < d; ++k) out[k] *= scale;
 }
 
@@ -126,7 +206,7 @@ static void apply_H(const double *in, double *out, int64_t d, int method)
 /* z = H x for N tokens. x: [N,d] of `dtype`; z: [N,d] double.  Returns 0, or -1 on bad arguments. */
 int wht_oracle_transform(const void *x, double *z, int64_t N, int64_t d, int dtype, int method)
 {
-    if (!x || !z || N < 0 || !is_pow2(d)) return -1;
+    if (!x || !z || N < 0 || !is_width(d)) return -1;
     int failed = 0;
 #pragma omp parallel
     {
@@ -192,7 +272,7 @@ int wht_oracle_backward(const void *dy, const void *x, const double *alpha,
                         double *dx, double *dalpha, double *dbeta,
                         int64_t N, int64_t d, int dtype, int method)
 {
-    if (!dy || !x || !alpha || N < 0 || !is_pow2(d)) return -1;
+    if (!dy || !x || !alpha || N < 0 || !is_width(d)) return -1;
     if ((dalpha == NULL) != (dbeta == NULL)) return -1;
     const int want_param_grads = dalpha != NULL;
     int nthreads = 1;

@@ -156,11 +156,13 @@ def test_unit_vectors_constants_linearity(d):
     assert np.allclose(lhs, rhs, atol=1e-12 * np.sqrt(d))
 
 
-def test_rejects_non_power_of_two():
-    with pytest.raises(ValueError):
-        oracle.transform(np.zeros((2, 768)))
-    with pytest.raises(ValueError):
-        oracle.forward(np.zeros((2, 12)), np.ones(12), np.zeros(12))
+def test_rejects_widths_without_a_definition():
+    # 2^n and 12 * 2^m have one; nothing else does (no Hadamard matrix of order 3, 6, 10 ...)
+    for d in (3, 6, 10, 20, 36, 100, 1000):
+        with pytest.raises(ValueError):
+            oracle.transform(np.zeros((2, d)))
+        with pytest.raises(ValueError):
+            oracle.forward(np.zeros((2, d)), np.ones(d), np.zeros(d))
 
 
 # ---------------------------------------------------------------- Eq. 1 special cases
