@@ -369,7 +369,8 @@ def main():
     if not args.no_extras:
         extras = {}
         extras["copy_ceiling"] = copy_ceiling(torch, wht)
-        others = [n for n in ("C4b_roofline", "C5_large", "C2_train", "C3_prefill") if n != args.workload]
+        others = [n for n in ("C4b_roofline", "C5_large", "C2_train", "C3_prefill",
+                              "W_tiny_768", "W_base_1536", "W_wide_6144") if n != args.workload]
         extras["workloads"] = []
         for name in others:
             b = Bench(torch, wht, synth, name)

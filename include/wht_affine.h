@@ -2,14 +2,27 @@
  * wht_affine.h -- C ABI of the Walsh-Hadamard output layer for AMD MI355X (gfx950).
  *
  * The layer replaces the dense attention output projection W_O (paper Sec. 4.1, Eq. 1):
- * for every token n, with x[n,:] the concatenated head outputs (d = heads * d_head, a power of two),
+ * for every token n, with x[n,:] the concatenated head outputs (d = heads * d_head),
  *
  *     z[n,:] = H x[n,:]                    H = H_raw / sqrt(d),  H_raw[j][k] = (-1)^popcount(j & k)
  *     y[n,:] = alpha (.) z[n,:] + beta     (Eq. 1; alpha, beta in R^d are the only parameters)
  *
- * H is the normalised Walsh-Hadamard matrix in Sylvester (natural) order -- the sign block drawn in
- * Fig. 1 -- so H^T H = I (Sec. 4.1) and H is symmetric.  It is never stored: the kernels run the
- * log2(d) add/subtract butterfly stages of Fig. 2.
+ * For d a power of two, H is the normalised Walsh-Hadamard matrix in Sylvester (natural) order --
+ * the sign block drawn in Fig. 1 -- so H^T H = I (Sec. 4.1) and H is symmetric.  It is never
+ * stored: the kernels run the log2(d) add/subtract butterfly stages of Fig. 2.
+ *
+ * Widths d = 12 * 2^m.  The paper also trains d = 768 and d = 1536 (Table 2) and does not say which
+ * matrix it uses there.  This library's reading, for bfloat16 tensors and d = 768 ... 6144:
+ *
+ *     H_raw = P12 (x) S_{2^m}      H_raw[j][k] = P12[j / 2^m][k / 2^m] * (-1)^popcount(j & k & (2^m - 1))
+ *
+ * i.e. the Sylvester transform inside each of the 12 contiguous blocks of 2^m features, and P12
+ * across the blocks; P12 is the symmetric order-12 Hadamard matrix of Paley's second construction
+ * over GF(5) with first row and column +1 (rows, as +/-):
+ *     ++++++++++++  +--+-+-+-+-+  +-+-++----++  ++--+--+-++-  +-+++-++----  +++---+--+-+
+ *     +---+++-++--  ++-++---+--+  +-----+++-++  ++-+-++---+-  +-++----+++-  +++--+-++---
+ * H = H_raw / sqrt(d) is again symmetric and orthogonal with entries +-1/sqrt(d), so Eq. 1 and the
+ * backward formulas below hold unchanged.
  *
  * Backward (the paper gives only the O(d log d) cost, Table 1; the formulas are Eq. 1's chain rule):
  *
@@ -29,8 +42,8 @@
  *   - The return value is a wht_status_t.  Arguments are validated before anything is enqueued, so
  *     a failed call has no side effects.  N = 0 is valid (backward then zero-fills dalpha, dbeta).
  *   - d must be a power of two with WHT_MIN_D <= d <= WHT_MAX_D (WHT_MAX_D_F32 for float32
- *     tensors, whose token groups take twice the LDS); anything else (including the paper's own
- *     d = 768 and 1536, for which it does not say how H is built) is WHT_ERR_BAD_DIM.
+ *     tensors, whose token groups take twice the LDS), or, for bfloat16 tensors only, 12 * 2^m with
+ *     WHT_MIN_D_TWELVE <= d <= WHT_MAX_D_TWELVE; anything else is WHT_ERR_BAD_DIM.
  */
 #ifndef WHT_AFFINE_H
 #define WHT_AFFINE_H
@@ -45,6 +58,8 @@ extern "C" {
 #define WHT_MIN_D 32
 #define WHT_MAX_D 16384        /* bfloat16 tensors */
 #define WHT_MAX_D_F32 8192     /* float32 tensors */
+#define WHT_MIN_D_TWELVE 768   /* d = 12 * 2^m, bfloat16 tensors: 768, 1536, 3072, 6144 */
+#define WHT_MAX_D_TWELVE 6144
 
 typedef enum {
     WHT_DTYPE_F32  = 0,   /* x, y, dy, dx are IEEE binary32 */
@@ -54,7 +69,7 @@ typedef enum {
 typedef enum {
     WHT_OK             = 0,
     WHT_ERR_NULL_PTR   = 1,   /* a required pointer is NULL */
-    WHT_ERR_BAD_DIM    = 2,   /* d not a power of two in [WHT_MIN_D, WHT_MAX_D(_F32)], or N < 0 */
+    WHT_ERR_BAD_DIM    = 2,   /* d outside the widths listed above for this dtype, or N < 0 */
     WHT_ERR_BAD_DTYPE  = 3,
     WHT_ERR_MISALIGNED = 4,   /* a tensor pointer is not 16-byte aligned */
     WHT_ERR_WORKSPACE  = 5,   /* workspace NULL or smaller than wht_affine_backward_workspace_bytes */

@@ -12,8 +12,10 @@
 // sum on small sizes.
 // Prints one line per configuration; exit status 0 iff all pass.
 #include <cmath>
+#include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <string>
 #include <vector>
 
 #include "wht_plan.h"
@@ -150,9 +152,76 @@ static bool check(const char* kind, const PlanDesc& pl, PhysFn phys, unsigned wo
     return ok;
 }
 
+// Rows of 12 * 2^m elements on 16 * 2^m slots: the slot map must be a bijection from the valid slots
+// onto the row, additive over bits, and "Sylvester butterflies on every slot bit but 4..7, the
+// order-12 round matrix along bits 3..7" must equal the definition
+//     out[j] = sum_k P12[j / L][k / L] * (-1)^popcount(j & k & (L - 1)) * x[k],   L = 2^m.
+static bool check_twelve(int n) {
+    const unsigned S = 1u << n, L = S / 16, D = 12 * L;
+    bool ok = true;
+    std::vector<int> hit(D, 0);
+    for (unsigned s = 0; s < S; ++s) {
+        if (!twelve_valid(s)) continue;
+        const unsigned el = twelve_elem(s, n);
+        if (el >= D) { ok = false; continue; }
+        ++hit[el];
+        for (int b = 0; b < n; ++b)        // additivity over single bits
+            if ((s >> b) & 1u)
+                if (twelve_elem(s, n) != twelve_elem(s & ~(1u << b), n) + twelve_elem(1u << b, n)) ok = false;
+        if ((s & 7u) == 0 && twelve_elem(s | 7u, n) != el + 7) ok = false;    // 8-element vectors stay whole
+    }
+    for (unsigned el = 0; el < D; ++el) if (hit[el] != 1) ok = false;
+    // the definition, on a small pseudo-random integer row (exact in double)
+    std::vector<double> x(D), want(D), slot(S, 0.0);
+    uint32_t rng = 12345u + (uint32_t)n;
+    for (unsigned k = 0; k < D; ++k) { rng = rng * 1664525u + 1013904223u; x[k] = (double)((int)(rng >> 24) - 128); }
+    if (n <= 12) {
+        for (unsigned j = 0; j < D; ++j) {
+            double acc = 0;
+            for (unsigned k = 0; k < D; ++k) {
+                const int p = ((paley12_minus_row(j / L) >> (k / L)) & 1u) ? -1 : 1;
+                const int sy = (__builtin_popcount(j & k & (L - 1)) & 1) ? -1 : 1;
+                acc += p * sy * x[k];
+            }
+            want[j] = acc;
+        }
+        for (unsigned s = 0; s < S; ++s) if (twelve_valid(s)) slot[s] = x[twelve_elem(s, n)];
+        for (int b = 0; b < n; ++b) {                       // Sylvester bits: all but 3..7
+            if (b >= 3 && b <= 7) continue;
+            for (unsigned s = 0; s < S; ++s)
+                if (!((s >> b) & 1u)) {
+                    const double a = slot[s], c = slot[s | (1u << b)];
+                    slot[s] = a + c; slot[s | (1u << b)] = a - c;
+                }
+        }
+        std::vector<double> out(S, 0.0);
+        for (unsigned s = 0; s < S; ++s) {                  // the 32 x 32 round along bits 3..7
+            const unsigned m_out = (s >> 3) & 31u, rest = s & ~(31u << 3);
+            double acc = 0;
+            for (unsigned m_in = 0; m_in < 32; ++m_in)
+                acc += twelve_round_entry(m_in, m_out) * slot[rest | (m_in << 3)];
+            out[s] = acc;
+        }
+        for (unsigned s = 0; s < S; ++s) {
+            if (twelve_valid(s)) { if (out[s] != want[twelve_elem(s, n)]) ok = false; }
+            else if (out[s] != 0.0) ok = false;             // padding stays zero
+        }
+    }
+    std::printf("twelve    n=%2d row=%u slots=%u %s\n", n, D, S, ok ? "ok" : "FAIL");
+    return ok;
+}
+
 int main(int argc, char** argv) {
+    if (argc > 1 && std::string(argv[1]) == "--p12") {     // print the order-12 factor, rows of +/-
+        for (unsigned r = 0; r < 12; ++r) {
+            for (unsigned c = 0; c < 12; ++c) std::putchar(((paley12_minus_row(r) >> c) & 1u) ? '-' : '+');
+            std::putchar('\n');
+        }
+        return 0;
+    }
     bool ok = true;
     const bool verbose = argc > 1;
+    for (int n = 10; n <= 13; ++n) ok = check_twelve(n) && ok;
     for (int v : {2, 3})
         for (int n = 5; n <= (v == 2 ? 13 : 14); ++n) {
             const PlanDesc pl = make_plan(n, log_e_for(n, v), v);

@@ -61,17 +61,17 @@ static int launch_backward(const void* dy, const void* x, const float* alpha, vo
                        static_cast<const T*>(dy), static_cast<const T*>(x), alpha, static_cast<T*>(dx),
                        static_cast<float*>(workspace), N);
     if (hipGetLastError() != hipSuccess) return WHT_ERR_LAUNCH;
-    if constexpr (C::D >= 4096)
-        hipLaunchKernelGGL(reduce_partials_kernel<16>, dim3(C::D / 64, 2), dim3(1024), 0, stream,
-                           static_cast<const float*>(workspace), grid, C::D, dalpha, dbeta);
+    if constexpr (C::kRow >= 4096)
+        hipLaunchKernelGGL(reduce_partials_kernel<16>, dim3((C::kRow + 63) / 64, 2), dim3(1024), 0, stream,
+                           static_cast<const float*>(workspace), grid, C::kRow, dalpha, dbeta);
     else
-        hipLaunchKernelGGL(reduce_partials_kernel<4>, dim3((C::D + 15) / 16, 2), dim3(1024), 0, stream,
-                           static_cast<const float*>(workspace), grid, C::D, dalpha, dbeta);
+        hipLaunchKernelGGL(reduce_partials_kernel<4>, dim3((C::kRow + 15) / 16, 2), dim3(1024), 0, stream,
+                           static_cast<const float*>(workspace), grid, C::kRow, dalpha, dbeta);
     return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
 }
 
 template <class C>
-static size_t workspace_for(int64_t N) { return (size_t)grid_for<C>(N, true) * 2 * C::D * sizeof(float); }
+static size_t workspace_for(int64_t N) { return (size_t)grid_for<C>(N, true) * 2 * C::kRow * sizeof(float); }
 
 enum class Op { Forward, Backward, Workspace };
 
@@ -129,12 +129,28 @@ static int dispatch_d(int logd, Op op, Args& a) {
     }
 }
 
-static int dispatch(int logd, int dtype, Op op, Args& a) {
-    return dtype == WHT_DTYPE_F32 ? dispatch_d<IoF32>(logd, op, a) : dispatch_d<IoBF16>(logd, op, a);
+// Rows of 12 * 2^m elements (bfloat16): matrix-core schedule on 16 * 2^m slots.
+static int dispatch_twelve(int logslots, Op op, Args& a) {
+    switch (logslots) {
+    case 10: return run<MfmaCfg<10, mfma_log_tiles(10), true>>(op, a);
+    case 11: return run<MfmaCfg<11, mfma_log_tiles(11), true>>(op, a);
+    case 12: return run<MfmaCfg<12, mfma_log_tiles(12), true>>(op, a);
+    case 13: return run<MfmaCfg<13, mfma_log_tiles(13), true>>(op, a);
+    default: return WHT_ERR_BAD_DIM;
+    }
+}
+
+// What a width d is to the library: log2 of the number of slots the schedule runs on, and whether
+// the row is a power of two or 12 * 2^m.
+struct Width { int logd; bool twelve; };
+
+static int dispatch(Width w, int dtype, Op op, Args& a) {
+    if (w.twelve) return dispatch_twelve(w.logd, op, a);
+    return dtype == WHT_DTYPE_F32 ? dispatch_d<IoF32>(w.logd, op, a) : dispatch_d<IoBF16>(w.logd, op, a);
 }
 
 static int log2_exact(int32_t d) {
-    if (d < WHT_MIN_D || d > WHT_MAX_D || (d & (d - 1)) != 0) return -1;
+    if (d < 1 || (d & (d - 1)) != 0) return -1;
     int l = 0;
     while ((1 << l) < d) ++l;
     return l;
@@ -142,11 +158,22 @@ static int log2_exact(int32_t d) {
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-static int check_dims(int64_t N, int32_t d, int32_t dtype, int* logd) {
+static int check_dims(int64_t N, int32_t d, int32_t dtype, Width* w) {
     if (dtype != WHT_DTYPE_F32 && dtype != WHT_DTYPE_BF16) return WHT_ERR_BAD_DTYPE;
-    *logd = log2_exact(d);
-    if (*logd < 0 || N < 0) return WHT_ERR_BAD_DIM;
-    if (dtype == WHT_DTYPE_F32 && d > WHT_MAX_D_F32) return WHT_ERR_BAD_DIM;
+    if (N < 0) return WHT_ERR_BAD_DIM;
+    const int l = log2_exact(d);
+    if (l >= 0) {
+        if (d < WHT_MIN_D || d > WHT_MAX_D) return WHT_ERR_BAD_DIM;
+        if (dtype == WHT_DTYPE_F32 && d > WHT_MAX_D_F32) return WHT_ERR_BAD_DIM;
+        *w = Width{l, false};
+        return WHT_OK;
+    }
+    // 12 * 2^m: bfloat16 only, 768 .. 6144
+    if (d % 12 != 0 || dtype != WHT_DTYPE_BF16 || d < WHT_MIN_D_TWELVE || d > WHT_MAX_D_TWELVE)
+        return WHT_ERR_BAD_DIM;
+    const int m = log2_exact(d / 12);
+    if (m < 0) return WHT_ERR_BAD_DIM;
+    *w = Width{m + 4, true};
     return WHT_OK;
 }
 
@@ -161,8 +188,8 @@ static int forward_common(const void* x, const float* alpha, const float* beta, 
                           bool with_resid, void* y, int64_t N, int32_t d, int32_t dtype, void* stream) {
     using namespace wht;
     if (!x || !alpha || !beta || !y || (with_resid && !resid)) return WHT_ERR_NULL_PTR;
-    int logd = 0;
-    if (int rc = check_dims(N, d, dtype, &logd)) return rc;
+    Width w{};
+    if (int rc = check_dims(N, d, dtype, &w)) return rc;
     if (!aligned16(x) || !aligned16(y) || !aligned16(alpha) || !aligned16(beta) ||
         (with_resid && !aligned16(resid)))
         return WHT_ERR_MISALIGNED;
@@ -170,7 +197,7 @@ static int forward_common(const void* x, const float* alpha, const float* beta, 
     Args a{};
     a.x = x; a.alpha = alpha; a.beta = beta; a.resid = with_resid ? resid : nullptr; a.y = y; a.N = N;
     a.stream = static_cast<hipStream_t>(stream);
-    return dispatch(logd, dtype, Op::Forward, a);
+    return dispatch(w, dtype, Op::Forward, a);
 }
 
 int wht_affine_forward(const void* x, const float* alpha, const float* beta, void* y, int64_t N,
@@ -185,11 +212,11 @@ int wht_affine_forward_residual(const void* x, const float* alpha, const float* 
 
 size_t wht_affine_backward_workspace_bytes(int64_t N, int32_t d, int32_t dtype) {
     using namespace wht;
-    int logd = 0;
-    if (check_dims(N, d, dtype, &logd) != WHT_OK || N == 0) return 0;
+    Width w{};
+    if (check_dims(N, d, dtype, &w) != WHT_OK || N == 0) return 0;
     Args a{};
     a.N = N;
-    dispatch(logd, dtype, Op::Workspace, a);
+    dispatch(w, dtype, Op::Workspace, a);
     return a.workspace_out;
 }
 
@@ -198,8 +225,8 @@ int wht_affine_backward(const void* dy, const void* x, const float* alpha, void*
                         size_t workspace_bytes, void* stream) {
     using namespace wht;
     if (!dy || !x || !alpha || !dx || !dalpha || !dbeta) return WHT_ERR_NULL_PTR;
-    int logd = 0;
-    if (int rc = check_dims(N, d, dtype, &logd)) return rc;
+    Width w{};
+    if (int rc = check_dims(N, d, dtype, &w)) return rc;
     if (!aligned16(dy) || !aligned16(x) || !aligned16(alpha) || !aligned16(dx) || !aligned16(dalpha) ||
         !aligned16(dbeta))
         return WHT_ERR_MISALIGNED;
@@ -214,7 +241,7 @@ int wht_affine_backward(const void* dy, const void* x, const float* alpha, void*
     Args a{};
     a.dy = dy; a.x = x; a.alpha = alpha; a.dx = dx; a.dalpha = dalpha; a.dbeta = dbeta; a.N = N;
     a.workspace = workspace; a.stream = s;
-    return dispatch(logd, dtype, Op::Backward, a);
+    return dispatch(w, dtype, Op::Backward, a);
 }
 
 int wht_affine_copy_baseline(const void* src, void* dst, size_t bytes, void* stream) {
@@ -235,7 +262,7 @@ const char* wht_affine_status_string(int status) {
     switch (status) {
     case WHT_OK:             return "ok";
     case WHT_ERR_NULL_PTR:   return "a required pointer is NULL";
-    case WHT_ERR_BAD_DIM:    return "d must be a power of two in [WHT_MIN_D, WHT_MAX_D] (WHT_MAX_D_F32 for float32) and N >= 0";
+    case WHT_ERR_BAD_DIM:    return "d must be a power of two in [WHT_MIN_D, WHT_MAX_D] (WHT_MAX_D_F32 for float32) or, for bfloat16, 12*2^m in [WHT_MIN_D_TWELVE, WHT_MAX_D_TWELVE]; N >= 0";
     case WHT_ERR_BAD_DTYPE:  return "dtype must be WHT_DTYPE_F32 or WHT_DTYPE_BF16";
     case WHT_ERR_MISALIGNED: return "tensor pointers must be 16-byte aligned";
     case WHT_ERR_WORKSPACE:  return "workspace is NULL or smaller than wht_affine_backward_workspace_bytes";

@@ -7,6 +7,10 @@
 //   - matrix-core schedule (bfloat16 I/O, d >= 1024): ten of the log2(d) stages run as two rounds
 //     of 32x32 +-1 products on the MFMA unit (exact products, float32 accumulation), the rest as
 //     register butterflies plus one LDS exchange across the waves of a token.
+// Widths d = 12 * 2^m (bfloat16, d >= 768; the paper's Table 2 trains d = 768 and 1536 and leaves the
+// matrix undefined there) use H_raw = P12 (x) S_{2^m}, P12 a symmetric order-12 Hadamard matrix: the
+// matrix-core schedule runs on a row padded to 16 * 2^m slots, with P12 inside the second round's
+// +-1 matrix (see MfmaCfg).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -99,6 +103,10 @@ struct Cfg {
     static constexpr int TPT = 1 << (n - e);    // threads per token
     static constexpr int BT = TPT > 256 ? TPT : 256;   // threads per workgroup
     static constexpr int G = BT / TPT;          // tokens per workgroup pass
+    static constexpr bool kTwelve = false;
+    static constexpr int kRow = D;              // elements per row in memory
+    static constexpr unsigned real(unsigned i) { return i; }
+    static constexpr bool valid(unsigned) { return true; }
     static constexpr unsigned phys(unsigned i) { return lds_phys_pad(i, v); }
     static constexpr unsigned kTokenWords = lds_words_pad(D, v);
     static constexpr unsigned kExchangeBytes = (P > 1 || G > 1) ? G * kTokenWords * 4u : 16u;
@@ -109,10 +117,20 @@ struct Cfg {
 };
 
 // Matrix-core schedule (bfloat16 I/O, d >= 1024): 2^LOGT MFMA tiles of 1024 elements per wave.
-template <int LOGD, int LOGT>
+//
+// TWELVE: the row in memory has 12 * 2^m elements (m = LOGD - 4) and the schedule runs on 2^LOGD
+// "slots".  Slot index s = (r_hi << 8) | (b << 4) | r_lo  <->  element b * 2^m + (r_hi << 4 | r_lo):
+// the block number b = 0..11 sits in slot bits 4..7 (b = 12..15 are empty slots, held as zeros and
+// never loaded or stored), so that the second round, which contracts slot bits 3..7, sees the pair
+// (element bit 3, block) and applies  P12 (x) H_2  there; every other slot bit is an ordinary
+// Sylvester bit.  Bits 6 and 7 are lane bits in both memory layouts, so a slot's validity is a
+// property of the lane: lanes 24..31 and 56..63 of every wave sit out the loads and stores, and
+// the others move 64 contiguous bytes per block.
+template <int LOGD, int LOGT, bool TWELVE = false>
 struct MfmaCfg {
     using io = IoBF16;
     static constexpr bool kMfma = true;
+    static constexpr bool kTwelve = TWELVE;
     static constexpr int n = LOGD, t = LOGT, e = 4 + LOGT, v = 3;
     static constexpr int w = n - 10 - t;        // log2(waves per token)
     static_assert(n >= 10 && w >= 0 && w <= 1 + t && e <= kMaxRegBits, "bad tile");
@@ -128,6 +146,13 @@ struct MfmaCfg {
     static_assert(TPT >= 64, "a token occupies whole waves");
     static constexpr int BT = TPT > 256 ? TPT : 256;
     static constexpr int G = BT / TPT;
+    static constexpr int kRow = TWELVE ? 3 * (D / 4) : D;       // elements per row in memory
+    static constexpr unsigned real(unsigned s) {                // slot index -> element index
+        return TWELVE ? twelve_elem(s, n) : s;
+    }
+    static constexpr bool valid(unsigned s) { return !TWELVE || twelve_valid(s); }
+    static_assert(!TWELVE || ((reg_mask(plan.ph[0], e) | reg_mask(plan.ph[P - 1], e)) & 0xC0u) == 0,
+                  "block bits 6 and 7 must be lane bits in the memory layouts");
     static constexpr unsigned phys(unsigned i) { return lds_phys_rot(i); }
     static constexpr unsigned kTokenWords = D;
     static constexpr unsigned kExchangeBytes = (P > 1 || G > 1) ? G * kTokenWords * 4u : 16u;
@@ -212,14 +237,18 @@ __device__ __forceinline__ void lds_get(float (&r)[C::E], const float* tok) {
 template <class C>
 struct ThreadMap {
     unsigned lds_off[kMaxPhases];
-    unsigned first_elem, last_elem;
+    unsigned first_elem, last_elem;     // offset within the row in memory
+    bool first_ok, last_ok;             // false for a thread whose slots are padding (12 * 2^m rows)
     __device__ __forceinline__ void init(unsigned t, unsigned slot) {
         static_for<0, C::P>([&](auto p) {
             constexpr int PH = decltype(p)::value;
             lds_off[PH] = slot * C::kTokenWords + C::phys(thread_elem_offset<C, PH>(t));
         });
-        first_elem = thread_elem_offset<C, 0>(t);
-        last_elem = thread_elem_offset<C, C::P - 1>(t);
+        const unsigned f = thread_elem_offset<C, 0>(t), l = thread_elem_offset<C, C::P - 1>(t);
+        first_elem = C::real(f);
+        last_elem = C::real(l);
+        first_ok = C::valid(f);
+        last_ok = C::valid(l);
     }
 };
 
@@ -272,12 +301,20 @@ typedef __attribute__((address_space(3))) void* lds_ptr;
 
 template <class C, int PH>
 __device__ __forceinline__ void stage_issue(unsigned char* wave_slot, const typename C::io::elem_t* row,
-                                            unsigned thread_elem) {
+                                            unsigned thread_elem, bool ok) {
     static_for<0, C::NV>([&](auto c) {
         constexpr int Cc = decltype(c)::value;
-        constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V);
-        __builtin_amdgcn_global_load_lds((global_cptr)(row + thread_elem + off),
-                                         (lds_ptr)(wave_slot + Cc * 1024), 16, 0, kStreamPolicy);
+        constexpr unsigned off = C::real(reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V));
+        if constexpr (C::kTwelve) {
+            // padding lanes fetch nothing (their stage slots are never used); the others fetch
+            // 32-byte pieces, two instructions per 128-byte line: cached, so the line is read once
+            if (ok)
+                __builtin_amdgcn_global_load_lds((global_cptr)(row + thread_elem + off),
+                                                 (lds_ptr)(wave_slot + Cc * 1024), 16, 0, 0);
+        } else {
+            __builtin_amdgcn_global_load_lds((global_cptr)(row + thread_elem + off),
+                                             (lds_ptr)(wave_slot + Cc * 1024), 16, 0, kStreamPolicy);
+        }
     });
 }
 
@@ -314,6 +351,16 @@ __device__ __forceinline__ void stage_read(uint4 (&raw)[C::NV], const unsigned c
     for (int c = 0; c < C::NV; ++c) raw[c] = make_uint4(v[c].x, v[c].y, v[c].z, v[c].w);
 }
 
+// Padding lanes of a 12 * 2^m row read stale LDS: replace it by zeros (the padding's value).
+template <class C>
+__device__ __forceinline__ void zero_padding(uint4 (&raw)[C::NV], bool ok) {
+    if constexpr (C::kTwelve) {
+#pragma unroll
+        for (int c = 0; c < C::NV; ++c)
+            if (!ok) raw[c] = make_uint4(0u, 0u, 0u, 0u);
+    }
+}
+
 // Wait until at most PENDING of this wave's vector-memory operations are outstanding.
 template <int PENDING>
 __device__ __forceinline__ void wait_vmem() {
@@ -327,24 +374,31 @@ __device__ __forceinline__ void unpack_all(float (&r)[C::E], const uint4 (&raw)[
     });
 }
 
-template <class C, int PH>
+// STREAM: non-temporal stores.  Rows of 12 * 2^m elements are written in 32-byte pieces; in the
+// forward kernel plain stores, which L2 merges into whole lines, measured 17 % faster at d = 6144,
+// in the backward kernel the non-temporal ones stayed ahead.
+template <class C, int PH, bool STREAM = true>
 __device__ __forceinline__ void global_put(const float (&r)[C::E], typename C::io::elem_t* row,
                                            unsigned thread_elem, bool active) {
     static_for<0, C::NV>([&](auto c) {
         constexpr int Cc = decltype(c)::value;
-        constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V);
-        if (active) stream_store16(row + thread_elem + off, C::io::pack(&r[Cc * C::V]));
+        constexpr unsigned off = C::real(reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V));
+        if (active) {
+            if constexpr (STREAM) stream_store16(row + thread_elem + off, C::io::pack(&r[Cc * C::V]));
+            else *reinterpret_cast<uint4*>(row + thread_elem + off) = C::io::pack(&r[Cc * C::V]);
+        }
     });
 }
 
 // float32 parameter vector -> registers in the layout of phase PH, times `scale`.
 template <class C, int PH>
 __device__ __forceinline__ void param_get(float (&r)[C::E], const float* p, unsigned thread_elem,
-                                          float scale) {
+                                          bool ok, float scale) {
     static_for<0, C::E / 4>([&](auto i) {
         constexpr int I = decltype(i)::value * 4;
-        constexpr unsigned off = reg_elem_offset(C::plan.ph[PH], C::e, I);
-        const float4 q = *reinterpret_cast<const float4*>(p + thread_elem + off);
+        constexpr unsigned off = C::real(reg_elem_offset(C::plan.ph[PH], C::e, I));
+        float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (!C::kTwelve || ok) q = *reinterpret_cast<const float4*>(p + thread_elem + off);
         r[I] = q.x * scale; r[I + 1] = q.y * scale; r[I + 2] = q.z * scale; r[I + 3] = q.w * scale;
     });
 }
@@ -393,6 +447,37 @@ __device__ __forceinline__ HadamardB make_hadamard_b() {
     return b;
 }
 
+// Second-round matrix for rows of 12 * 2^m elements.  The round contracts slot bits 3..7: bit 3 is
+// an ordinary Sylvester bit, bits 4..7 are the block number, so with m = bit3 + 2 * block the
+// matrix is  M[m_in][m_out] = (-1)^(bit3_in & bit3_out) * P12[block_in][block_out], and zero when
+// either block is one of the four empty ones.  In the operand layout above the second round's K
+// index arrives with bits 2 and 3 exchanged and its column index in natural order, hence
+// B[k][j] = M[swap23(k)][j], M = twelve_round_entry (wht_plan.h).
+__device__ __forceinline__ HadamardB make_paley_b(const HadamardB& sylvester) {
+    const unsigned lane = threadIdx.x & 63u;
+    const unsigned j = lane & 31u, kg = lane >> 5;
+    uint32_t w[2][4];
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            uint32_t pair = 0;
+#pragma unroll
+            for (int odd = 0; odd < 2; ++odd) {
+                const unsigned k = (2u * p) | (unsigned)odd | (kg << 3) | ((unsigned)half << 4);
+                const unsigned m_in = (k & 0x13u) | ((k & 4u) << 1) | ((k & 8u) >> 1);
+                const int sign = twelve_round_entry(m_in, j);
+                const uint32_t entry = sign == 0 ? 0u : (sign < 0 ? 0xBF80u : 0x3F80u);   // bf16 0, -1, +1
+                pair |= entry << (16 * odd);
+            }
+            w[half][p] = pair;
+        }
+    HadamardB b = sylvester;             // same split selectors
+    b.k_lo = __builtin_bit_cast(bf16x8, make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]));
+    b.k_hi = __builtin_bit_cast(bf16x8, make_uint4(w[1][0], w[1][1], w[1][2], w[1][3]));
+    return b;
+}
+
 // One round on bfloat16 data straight from memory: products and sums are exact up to the
 // accumulator's float32 rounding.
 __device__ __forceinline__ f32x16 hadamard_round_bf16(const uint4& a_lo, const uint4& a_hi,
@@ -432,13 +517,14 @@ __device__ __forceinline__ f32x16 hadamard_round_f32(const float* v, const Hadam
     return acc;
 }
 
-// Both rounds on every tile of the thread: bits 0..9 of the element index.  Round 1 of every tile
+// Both rounds on every tile of the thread: bits 0..9 of the element index.  b is the Sylvester
+// matrix; b2, the second round's matrix, is the same except for rows of 12 * 2^m elements.  Round 1 of every tile
 // is issued before any round 2, so that one tile's split has the other tile's matrix instructions
 // to overlap with.  (Explicit MFMA/VALU interleave hints on top of this measured no gain.)
 //   from raw bfloat16 (the forward input x): round 1 needs no split
 template <class C>
 __device__ __forceinline__ void mfma_rounds_from_bf16(float (&r)[C::E], const uint4 (&raw)[C::NV],
-                                                      const HadamardB& b) {
+                                                      const HadamardB& b, const HadamardB& b2) {
     f32x16 d1[C::T];
     static_for<0, C::T>([&](auto tile) {
         constexpr int Tl = decltype(tile)::value;
@@ -449,14 +535,15 @@ __device__ __forceinline__ void mfma_rounds_from_bf16(float (&r)[C::E], const ui
         float v[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) v[i] = d1[Tl][i];
-        const f32x16 d2 = hadamard_round_f32(v, b);
+        const f32x16 d2 = hadamard_round_f32(v, b2);
 #pragma unroll
         for (int i = 0; i < 16; ++i) r[16 * Tl + i] = d2[i];
     });
 }
 //   from float32 registers in the first layout (the backward pass's alpha' (.) dy)
 template <class C>
-__device__ __forceinline__ void mfma_rounds_from_f32(float (&r)[C::E], const HadamardB& b) {
+__device__ __forceinline__ void mfma_rounds_from_f32(float (&r)[C::E], const HadamardB& b,
+                                                     const HadamardB& b2) {
     f32x16 d1[C::T];
     static_for<0, C::T>([&](auto tile) {
         constexpr int Tl = decltype(tile)::value;
@@ -467,7 +554,7 @@ __device__ __forceinline__ void mfma_rounds_from_f32(float (&r)[C::E], const Had
         float v[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) v[i] = d1[Tl][i];
-        const f32x16 d2 = hadamard_round_f32(v, b);
+        const f32x16 d2 = hadamard_round_f32(v, b2);
 #pragma unroll
         for (int i = 0; i < 16; ++i) r[16 * Tl + i] = d2[i];
     });
@@ -477,8 +564,8 @@ __device__ __forceinline__ void mfma_rounds_from_f32(float (&r)[C::E], const Had
 template <class C, bool TRAILING_BARRIER>
 __device__ __forceinline__ void transform_from_raw(float (&r)[C::E], const uint4 (&raw)[C::NV],
                                                    float* lds, const ThreadMap<C>& tm,
-                                                   const HadamardB& b) {
-    if constexpr (C::kMfma) mfma_rounds_from_bf16<C>(r, raw, b);
+                                                   const HadamardB& b, const HadamardB& b2) {
+    if constexpr (C::kMfma) mfma_rounds_from_bf16<C>(r, raw, b, b2);
     else                    unpack_all<C>(r, raw);
     transform<C, true, TRAILING_BARRIER>(r, lds, tm);
 }
@@ -486,13 +573,18 @@ __device__ __forceinline__ void transform_from_raw(float (&r)[C::E], const uint4
 // registers in the last layout -> H_raw (.) in the first layout.
 template <class C>
 __device__ __forceinline__ void transform_back(float (&r)[C::E], float* lds, const ThreadMap<C>& tm,
-                                               const HadamardB& b) {
+                                               const HadamardB& b, const HadamardB& b2) {
     transform<C, false, false>(r, lds, tm);
-    if constexpr (C::kMfma) mfma_rounds_from_f32<C>(r, b);
+    if constexpr (C::kMfma) mfma_rounds_from_f32<C>(r, b, b2);
 }
 
 template <class C>
 __device__ __forceinline__ float inv_sqrt_d() {
+    if constexpr (C::kTwelve) {
+        // d = 3 * 2^(n-2): 1/sqrt(3) or 1/sqrt(6), rounded once, times a power of two
+        return ((C::n - 2) % 2 == 0) ? 0.57735026918962576451f / float(1 << ((C::n - 2) / 2))
+                                     : 0.40824829046386301637f / float(1 << ((C::n - 2) / 2));
+    }
     // exact power of two for even log2 d; one rounding of 1/sqrt(2) * 2^-k otherwise
     return (C::n % 2 == 0) ? 1.0f / float(1 << (C::n / 2))
                            : 0.70710678118654752440f / float(1 << (C::n / 2));
@@ -542,8 +634,10 @@ __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::el
     Walker<C> wk{N, (N + C::G - 1) / C::G, threadIdx.x / C::TPT};
     ThreadMap<C> tm;
     tm.init(t, wk.slot);
-    HadamardB hb{};
+    HadamardB hb{}, hbp{};
     if constexpr (C::kMfma) hb = make_hadamard_b();
+    if constexpr (C::kTwelve) hbp = make_paley_b(hb);
+    const HadamardB& hb2 = C::kTwelve ? hbp : hb;
     unsigned char* stage = stage_buf + (threadIdx.x >> 6) * (C::NV * 1024);
     unsigned char* stage_r = stage_r_buf + (RESID ? (threadIdx.x >> 6) * (C::NV * 1024) : 0);
 
@@ -551,25 +645,28 @@ __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::el
     const int64_t step = gridDim.x;
     int64_t grp = blockIdx.x;
     if (grp < wk.groups) {
-        stage_issue<C, 0>(stage, x + wk.row(grp) * C::D, tm.first_elem);
-        if constexpr (RESID) stage_issue<C, LAST>(stage_r, resid + wk.row(grp) * C::D, tm.last_elem);
+        stage_issue<C, 0>(stage, x + wk.row(grp) * C::kRow, tm.first_elem, tm.first_ok);
+        if constexpr (RESID)
+            stage_issue<C, LAST>(stage_r, resid + wk.row(grp) * C::kRow, tm.last_elem, tm.last_ok);
     }
 
     float a[C::E], b[C::E];
-    param_get<C, LAST>(a, alpha, tm.last_elem, inv_sqrt_d<C>());
-    param_get<C, LAST>(b, beta, tm.last_elem, 1.0f);
+    param_get<C, LAST>(a, alpha, tm.last_elem, tm.last_ok, inv_sqrt_d<C>());
+    param_get<C, LAST>(b, beta, tm.last_elem, tm.last_ok, 1.0f);
     wait_vmem<0>();
     for (; grp < wk.groups; grp += step) {
         const bool more = grp + step < wk.groups;
         uint4 raw[C::NV], rraw[RESID ? C::NV : 1];
         stage_read<C>(raw, stage);
+        zero_padding<C>(raw, tm.first_ok);
         if constexpr (RESID) stage_read<C>(rraw, stage_r);
         if (more) {
-            stage_issue<C, 0>(stage, x + wk.row(grp + step) * C::D, tm.first_elem);
-            if constexpr (RESID) stage_issue<C, LAST>(stage_r, resid + wk.row(grp + step) * C::D, tm.last_elem);
+            stage_issue<C, 0>(stage, x + wk.row(grp + step) * C::kRow, tm.first_elem, tm.first_ok);
+            if constexpr (RESID)
+                stage_issue<C, LAST>(stage_r, resid + wk.row(grp + step) * C::kRow, tm.last_elem, tm.last_ok);
         }
         float r[C::E];
-        transform_from_raw<C, true>(r, raw, lds, tm, hb);
+        transform_from_raw<C, true>(r, raw, lds, tm, hb, hb2);
         if constexpr (RESID) {
             float res[C::E];
             unpack_all<C>(res, rraw);
@@ -581,7 +678,7 @@ __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::el
         }
         if (more) wait_vmem<0>();
         const int64_t tok = wk.token(grp);
-        global_put<C, LAST>(r, y + tok * C::D, tm.last_elem, tok < N);
+        global_put<C, LAST, !C::kTwelve>(r, y + tok * C::kRow, tm.last_elem, tok < N && tm.last_ok);
     }
 }
 
@@ -600,7 +697,7 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
                                                          const typename C::io::elem_t* x,
                                                          const float* __restrict__ alpha,
                                                          typename C::io::elem_t* dx,
-                                                         float* __restrict__ partials,   // [grid][2][D]
+                                                         float* __restrict__ partials,   // [grid][2][kRow]
                                                          int64_t N) {
     __shared__ __align__(16) float lds[C::kExchangeBytes / 4];
     __shared__ __align__(16) unsigned char stage_x_buf[C::kStageBytes];
@@ -610,20 +707,22 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
     Walker<C> wk{N, (N + C::G - 1) / C::G, threadIdx.x / C::TPT};
     ThreadMap<C> tm;
     tm.init(t, wk.slot);
-    HadamardB hb{};
+    HadamardB hb{}, hbp{};
     if constexpr (C::kMfma) hb = make_hadamard_b();
+    if constexpr (C::kTwelve) hbp = make_paley_b(hb);
+    const HadamardB& hb2 = C::kTwelve ? hbp : hb;
     unsigned char* stage_x = stage_x_buf + (threadIdx.x >> 6) * (C::NV * 1024);
     unsigned char* stage_g = stage_g_buf + (threadIdx.x >> 6) * (C::NV * 1024);
 
     const int64_t step = gridDim.x;
     int64_t grp = blockIdx.x;
     if (grp < wk.groups) {
-        stage_issue<C, 0>(stage_x, x + wk.row(grp) * C::D, tm.first_elem);
-        stage_issue<C, LAST>(stage_g, dy + wk.row(grp) * C::D, tm.last_elem);
+        stage_issue<C, 0>(stage_x, x + wk.row(grp) * C::kRow, tm.first_elem, tm.first_ok);
+        stage_issue<C, LAST>(stage_g, dy + wk.row(grp) * C::kRow, tm.last_elem, tm.last_ok);
     }
 
     float a[C::E], da[C::E], db[C::E];
-    param_get<C, LAST>(a, alpha, tm.last_elem, inv_sqrt_d<C>());
+    param_get<C, LAST>(a, alpha, tm.last_elem, tm.last_ok, inv_sqrt_d<C>());
 #pragma unroll
     for (int i = 0; i < C::E; ++i) { da[i] = 0.0f; db[i] = 0.0f; }
     wait_vmem<0>();
@@ -632,12 +731,14 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
         uint4 raw[C::NV], graw[C::NV];
         stage_read<C>(raw, stage_x);
         stage_read<C>(graw, stage_g);
+        zero_padding<C>(raw, tm.first_ok);
+        zero_padding<C>(graw, tm.last_ok);
         if (more) {
-            stage_issue<C, 0>(stage_x, x + wk.row(grp + step) * C::D, tm.first_elem);
-            stage_issue<C, LAST>(stage_g, dy + wk.row(grp + step) * C::D, tm.last_elem);
+            stage_issue<C, 0>(stage_x, x + wk.row(grp + step) * C::kRow, tm.first_elem, tm.first_ok);
+            stage_issue<C, LAST>(stage_g, dy + wk.row(grp + step) * C::kRow, tm.last_elem, tm.last_ok);
         }
         float r[C::E], g[C::E];
-        transform_from_raw<C, false>(r, raw, lds, tm, hb);    // r = H_raw x, last layout
+        transform_from_raw<C, false>(r, raw, lds, tm, hb, hb2);   // r = H_raw x, last layout
         unpack_all<C>(g, graw);
         const int64_t tok = wk.token(grp);
         const bool active = C::G == 1 || tok < N;             // one slot per workgroup: never ragged
@@ -653,24 +754,25 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
             db[i] += g[i];
             g[i] *= a[i];
         }
-        transform_back<C>(g, lds, tm, hb);                    // g = H_raw(alpha' dy), first layout
+        transform_back<C>(g, lds, tm, hb, hb2);               // g = H_raw(alpha' dy), first layout
         if (more) wait_vmem<0>();
-        global_put<C, 0>(g, dx + tok * C::D, tm.first_elem, active);
+        global_put<C, 0>(g, dx + tok * C::kRow, tm.first_elem, active && tm.first_ok);
     }
 
     // Sum the G token slots of this workgroup through LDS, then write the workgroup's row.
     if constexpr (C::G > 1) __syncthreads();      // the last exchange's reads are done everywhere
     const float s = inv_sqrt_d<C>();
-    float* row = partials + (size_t)blockIdx.x * 2 * C::D;
+    float* row = partials + (size_t)blockIdx.x * 2 * C::kRow;
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
         if constexpr (C::G == 1) {
             static_for<0, C::E / 4>([&](auto i) {
                 constexpr int I = decltype(i)::value * 4;
-                constexpr unsigned off = reg_elem_offset(C::plan.ph[LAST], C::e, I);
+                constexpr unsigned off = C::real(reg_elem_offset(C::plan.ph[LAST], C::e, I));
                 const float4 q = which == 0 ? make_float4(da[I] * s, da[I + 1] * s, da[I + 2] * s, da[I + 3] * s)
                                             : make_float4(db[I], db[I + 1], db[I + 2], db[I + 3]);
-                *reinterpret_cast<float4*>(row + which * C::D + tm.last_elem + off) = q;
+                if (!C::kTwelve || tm.last_ok)
+                    *reinterpret_cast<float4*>(row + which * C::kRow + tm.last_elem + off) = q;
             });
         } else {
             if (which == 0) lds_put<C, LAST>(da, lds + tm.lds_off[LAST]);
@@ -680,7 +782,7 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
                 float acc = 0.0f;
 #pragma unroll
                 for (int gslot = 0; gslot < C::G; ++gslot) acc += lds[gslot * C::kTokenWords + C::phys(j)];
-                row[which * C::D + j] = which == 0 ? acc * s : acc;
+                if (C::valid(j)) row[which * C::kRow + C::real(j)] = which == 0 ? acc * s : acc;
             }
             __syncthreads();
         }

@@ -178,6 +178,31 @@ constexpr PlanDesc make_mfma_plan(int n, int t) {
 // tiles per wave (log2) used for a given log2 d
 constexpr int mfma_log_tiles(int logd) { return logd <= 10 ? 0 : (logd <= 13 ? 1 : 2); }
 
+// ---- rows of 12 * 2^m elements on 2^n = 16 * 2^m slots ----------------------------------------
+// Slot index s = (r_hi << 8) | (b << 4) | r_lo  <->  element b * 2^m + (r_hi << 4 | r_lo), m = n - 4:
+// the block number b = 0..11 occupies slot bits 4..7, b = 12..15 are padding.  A bit permutation, so
+// additive over disjoint bit sets like the LDS maps below.
+constexpr unsigned twelve_elem(unsigned s, int n) {
+    return (((s >> 4) & 15u) << (n - 4)) | ((s >> 8) << 4) | (s & 15u);
+}
+constexpr bool twelve_valid(unsigned s) { return ((s >> 6) & 3u) != 3u; }
+
+// P12: symmetric order-12 Hadamard matrix (Paley's second construction over GF(5)), first row and
+// column +1.  Bit c of row r's mask is set where P12[r][c] = -1.
+constexpr unsigned paley12_minus_row(unsigned r) {
+    constexpr unsigned rows[12] = {0x000, 0x556, 0x3ca, 0x96c, 0xf22, 0x5b8,
+                                   0xc8e, 0x6e4, 0x23e, 0xb94, 0x8f2, 0xe58};
+    return rows[r];
+}
+// Entry of the matrix the second matrix-core round applies along slot bits 3..7 of such a row:
+// index m = bit3 + 2 * block;  (-1)^(bit3_in & bit3_out) * P12[block_in][block_out], 0 on padding.
+constexpr int twelve_round_entry(unsigned m_in, unsigned m_out) {
+    const unsigned bi = m_in >> 1, bo = m_out >> 1;
+    if (bi >= 12u || bo >= 12u) return 0;
+    const unsigned minus = ((paley12_minus_row(bi) >> bo) ^ (m_in & m_out)) & 1u;
+    return minus ? -1 : 1;
+}
+
 // ---- LDS address maps -------------------------------------------------------------------------
 // Both are linear in the bits of i (phys(a | b) = phys(a) + phys(b) for disjoint a, b) and keep four
 // consecutive elements in one aligned 16-byte group.

@@ -41,6 +41,11 @@ WORKLOADS = {w.name: w for w in [
     Workload("C4_decode_n256", 256, 4096, "bf16", False),
     Workload("C4b_roofline", 32768, 4096, "bf16", True, note="added bandwidth-bound shape at d=4096"),
     Workload("C5_large", 4 * 8192, 8192, "bf16", True, note="B=4 S=8192, 64 heads x 128"),
+    # widths d = 12 * 2^m: the paper's own Tiny and Base models (Table 2) at a training-sized token
+    # batch, and a wide one next to C5
+    Workload("W_tiny_768", 32 * 1024, 768, "bf16", True, note="Table 2 Tiny: 12 heads x 64, B=32 S=1024"),
+    Workload("W_base_1536", 32 * 1024, 1536, "bf16", True, note="Table 2 Base: 16 heads x 96, B=32 S=1024"),
+    Workload("W_wide_6144", 4 * 8192, 6144, "bf16", True, note="48 heads x 128, B=4 S=8192"),
 ]}
 
 

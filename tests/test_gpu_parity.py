@@ -22,6 +22,9 @@ def _method(d):
     return "matrix" if d <= 512 else "fast"
 
 
+TWELVE_D = [768, 1536, 3072, 6144]      # d = 12 * 2^m: H = P12 (x) Sylvester, bfloat16 only
+
+
 def run_forward(inp):
     x = to_gpu(inp.x, inp.dtype)
     a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
@@ -74,6 +77,79 @@ def test_backward_every_d(d, dtype):
     N = 67 if d <= 2048 else 9
     _announce(f"backward d={d} {dtype} N={N}")
     check_backward_full(synth.make_inputs(N, d, dtype, seed=d + 1), f"bwd d={d} {dtype}")
+
+
+@pytest.mark.parametrize("d", TWELVE_D)
+def test_forward_twelve_widths(d):
+    # 67 / 9 tokens: ragged last pass for every tokens-per-workgroup value (4 at d = 768, else 1)
+    N = 67 if d <= 1536 else 9
+    _announce(f"forward d={d} (12 * 2^m) bf16 N={N}")
+    inp = synth.make_inputs(N, d, "bf16", seed=d, backward=False)
+    y = run_forward(inp)
+    # the first tokens against the O(d^2) definition, everything against the fast method
+    ref_def = oracle.forward(inp.x[:3], inp.alpha, inp.beta, "matrix")
+    assert_io_close(y[:3], ref_def, "bf16", f"fwd d={d} y vs definition")
+    assert_io_close(y, oracle.forward(inp.x, inp.alpha, inp.beta, "fast"), "bf16", f"fwd d={d} y")
+
+
+@pytest.mark.parametrize("d", TWELVE_D)
+def test_backward_twelve_widths(d):
+    N = 67 if d <= 1536 else 9
+    _announce(f"backward d={d} (12 * 2^m) bf16 N={N}")
+    check_backward_full(synth.make_inputs(N, d, "bf16", seed=d + 1), f"bwd d={d}")
+
+
+@pytest.mark.parametrize("d", [768, 6144])
+def test_twelve_widths_unit_vectors_and_blocks(d):
+    # one-hot inputs make every sign of a column of H visible in y (alpha = 1, beta = 0): any wrong
+    # entry of the order-12 factor, block order or slot mapping shows up as a sign flip
+    m = d // 12
+    ks = [0, 1, 8, m - 1, m, 3 * m + 5, 7 * m + 16, 11 * m, d - 1]
+    x = np.zeros((len(ks), d), dtype=np.float32)
+    for row, k in enumerate(ks):
+        x[row, k] = 1.0
+    _announce(f"one-hot columns d={d}")
+    xb = synth.f32_to_bf16_bits(x)
+    y = wht.wht_affine_forward(to_gpu(xb, "bf16"), torch.ones(d, device="cuda"), torch.zeros(d, device="cuda"))
+    torch.cuda.synchronize()
+    ref = oracle.forward(xb, np.ones(d), np.zeros(d), "matrix")
+    got = to_f64(y)
+    assert np.array_equal(np.sign(got), np.sign(ref))
+    assert_io_close(y, ref, "bf16", f"one-hot d={d}")
+
+
+@pytest.mark.parametrize("d,N", [(768, 263), (1536, 67), (6144, 35)])
+def test_forward_residual_twelve_widths(d, N):
+    _announce(f"forward+residual d={d} (12 * 2^m) N={N}")
+    inp = synth.make_inputs(N, d, "bf16", seed=d + 7)
+    x, resid = to_gpu(inp.x, "bf16"), to_gpu(inp.dy, "bf16")
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    y = wht.wht_affine_forward_residual(x, a, b, resid)
+    torch.cuda.synchronize()
+    ref = oracle.forward_residual(inp.x, inp.alpha, inp.beta, inp.dy, "fast")
+    assert_io_close(y, ref, "bf16", f"fwd+resid d={d}")
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 5, 127, 129, 1031])
+def test_twelve_widths_reduction_over_odd_token_counts(N):
+    _announce(f"reduction N={N} d=768")
+    check_backward_full(synth.make_inputs(N, 768, "bf16", seed=N), f"bwd N={N} d=768")
+
+
+def test_twelve_width_full_size_sampled():
+    # the paper's Base width at a training-sized batch: sampled tokens for y and dx, full reductions
+    N, d = 32768, 1536
+    _announce(f"full size N={N} d={d} (sampled tokens)")
+    inp = synth.make_inputs(N, d, "bf16", seed=0)
+    idx = _sample_tokens(N, 64, seed=6)
+    y = run_forward(inp)
+    assert_io_close(y[torch.from_numpy(idx).cuda()], oracle.forward(inp.x[idx], inp.alpha, inp.beta, "fast"),
+                    "bf16", "d=1536 y (sampled tokens)")
+    dx, da, db = run_backward(inp)
+    rdx, rda, rdb = oracle.backward(inp.dy, inp.x, inp.alpha, "fast")
+    assert_io_close(dx[torch.from_numpy(idx).cuda()], rdx[idx], "bf16", "d=1536 dx (sampled tokens)")
+    assert_grad_close(da, rda, "d=1536 dalpha")
+    assert_grad_close(db, rdb, "d=1536 dbeta")
 
 
 @pytest.mark.parametrize("N", [1, 2, 3, 127, 128, 129, 1031])
@@ -296,8 +372,8 @@ def test_boundary_errors_on_gpu():
     assert float(before_da.min()) == 3.0
     assert binding.wht_affine_forward_raw(x.data_ptr() + 4, a.data_ptr(), a.data_ptr(), x.data_ptr(), N, d, 0) == 4
     with pytest.raises(wht.WhtAffineError):
-        wht.wht_affine_forward(torch.zeros(2, 768, device="cuda"), torch.ones(768, device="cuda"),
-                               torch.ones(768, device="cuda"))
+        wht.wht_affine_forward(torch.zeros(2, 96, device="cuda"), torch.ones(96, device="cuda"),
+                               torch.ones(96, device="cuda"))
 
 
 def test_copy_baseline_copies():

@@ -44,8 +44,13 @@ P = 0x1000   # a 16-byte-aligned non-null fake address: validation fails before 
     ((P, 0, P, P, 4, 256, 0), NULLP),
     ((P, P, 0, P, 4, 256, 0), NULLP),
     ((P, P, P, 0, 4, 256, 0), NULLP),
-    ((P, P, P, P, 4, 768, 1), DIM),        # the paper's own non-power-of-two width: rejected
-    ((P, P, P, P, 4, 1536, 1), DIM),
+    ((P, P, P, P, 4, 768, 0), DIM),        # 12 * 2^m widths: bfloat16 only ...
+    ((P, P, P, P, 4, 384, 1), DIM),        # ... from 768 ...
+    ((P, P, P, P, 4, 12288, 1), DIM),      # ... to 6144
+    ((P, P, P, P, 4, 1000, 1), DIM),       # neither 2^n nor 12 * 2^m
+    ((P, P, P, P, 4, 1280, 1), DIM),       # 5 * 2^8
+    ((P, P, P, P, 0, 768, 1), OK),         # accepted width, N = 0
+    ((P, P, P, P, 0, 6144, 1), OK),
     ((P, P, P, P, 4, 16, 0), DIM),         # below WHT_MIN_D
     ((P, P, P, P, 4, 32768, 1), DIM),      # above WHT_MAX_D
     ((P, P, P, P, 4, 16384, 0), DIM),      # above WHT_MAX_D_F32
@@ -67,7 +72,8 @@ def test_forward_residual_argument_validation():
     call = binding.wht_affine_forward_residual_raw
     assert call(P, P, P, 0, P, 4, 256, 1) == NULLP            # resid is required here
     assert call(P, P, P, P + 8, P, 4, 256, 1) == ALIGN
-    assert call(P, P, P, P, P, 4, 768, 1) == DIM
+    assert call(P, P, P, P, P, 4, 768, 0) == DIM
+    assert call(P, P, P, P, P, 0, 1536, 1) == OK
     assert call(P, P, P, P, P, 4, 256, 3) == DTYPE
     assert call(P, P, P, P, P, 0, 256, 1) == OK
 
@@ -94,6 +100,10 @@ def test_workspace_query():
     assert q(1, 8192, 1) == 2 * 8192 * 4
     assert q(32768, 8192, 1) >= q(64, 8192, 1) > 0
     assert q(32768, 8192, 1) <= 64 << 20
+    # rows of 12 * 2^m elements: the partial rows have the row's real length
+    assert q(1, 6144, 1) == 2 * 6144 * 4
+    assert q(4, 768, 1) == 2 * 768 * 4            # four tokens share a workgroup at d = 768
+    assert q(10, 768, 0) == 0 and q(10, 12288, 1) == 0
 
 
 def test_missing_library_fails_loudly(monkeypatch):
