@@ -17,23 +17,33 @@ namespace wht {
 constexpr int kNumCU = 256;             // MI355X
 
 // Workgroups launched per CU (the grid is persistent: each workgroup strides over token groups).
-// The defaults are the measured optima; the environment variables exist for tuning runs only.
-static int env_int(const char* name, int fallback) {
+// The per-configuration defaults (C::kFwdGroupsPerCU, C::kBwdGroupsPerCU) are the measured optima;
+// the environment variables exist for tuning runs only.
+static int env_int(const char* name, int fallback, int hi) {
     const char* v = getenv(name);
     if (!v || !*v) return fallback;
     const int x = atoi(v);
-    return (x >= 1 && x <= 256) ? x : fallback;
+    return (x >= 1 && x <= hi) ? x : fallback;
 }
-static int groups_per_cu(bool backward) {
-    static const int fwd = env_int("WHT_AFFINE_FWD_GROUPS_PER_CU", 8);
-    static const int bwd = env_int("WHT_AFFINE_BWD_GROUPS_PER_CU", 2);
+static int groups_per_cu_override(bool backward) {      // 0 = not set
+    static const int fwd = env_int("WHT_AFFINE_FWD_GROUPS_PER_CU", 0, 256);
+    static const int bwd = env_int("WHT_AFFINE_BWD_GROUPS_PER_CU", 0, 256);
+    return backward ? bwd : fwd;
+}
+// Absolute grid size, overriding the per-CU figure (0 = not set).
+static int grid_override(bool backward) {
+    static const int fwd = env_int("WHT_AFFINE_FWD_GRID", 0, 65536);
+    static const int bwd = env_int("WHT_AFFINE_BWD_GRID", 0, 65536);
     return backward ? bwd : fwd;
 }
 
 template <class C>
 static int grid_for(int64_t N, bool backward) {
     const int64_t groups = (N + C::G - 1) / C::G;
-    const int64_t cap = (int64_t)kNumCU * groups_per_cu(backward);
+    const int forced = grid_override(backward);
+    const int per_cu_env = groups_per_cu_override(backward);
+    const int per_cu = per_cu_env ? per_cu_env : (backward ? C::kBwdGroupsPerCU : C::kFwdGroupsPerCU);
+    const int64_t cap = forced ? forced : (int64_t)kNumCU * per_cu;
     return (int)(groups < cap ? groups : cap);
 }
 

@@ -104,6 +104,9 @@ struct Cfg {
     static constexpr int BT = TPT > 256 ? TPT : 256;   // threads per workgroup
     static constexpr int G = BT / TPT;          // tokens per workgroup pass
     static constexpr bool kTwelve = false;
+    // persistent-grid size in workgroups per CU (measured optima, N = 16384..32768 tokens)
+    static constexpr int kFwdGroupsPerCU = v == 2 ? (n >= 13 ? 8 : 4) : (n <= 9 ? 2 : 8);
+    static constexpr int kBwdGroupsPerCU = v == 2 ? 1 : 2;
     static constexpr int kRow = D;              // elements per row in memory
     static constexpr unsigned real(unsigned i) { return i; }
     static constexpr bool valid(unsigned) { return true; }
@@ -146,6 +149,10 @@ struct MfmaCfg {
     static_assert(TPT >= 64, "a token occupies whole waves");
     static constexpr int BT = TPT > 256 ? TPT : 256;
     static constexpr int G = BT / TPT;
+    // persistent-grid size in workgroups per CU (measured optima at N = 32768 tokens: more
+    // workgroups than this only add concurrent streams to the memory system)
+    static constexpr int kFwdGroupsPerCU = 2;
+    static constexpr int kBwdGroupsPerCU = TWELVE ? (n == 11 ? 1 : 2) : ((n == 11 || n >= 13) ? 1 : 2);
     static constexpr int kRow = TWELVE ? 3 * (D / 4) : D;       // elements per row in memory
     static constexpr unsigned real(unsigned s) {                // slot index -> element index
         return TWELVE ? twelve_elem(s, n) : s;

@@ -11,7 +11,8 @@ Two sub-commands:
              summary kept under profiles/ (per-kernel average duration; HBM bytes per launch scaled
              by what the same counter reads for the copy kernel; VALU / MFMA / LDS activity):
                  python3 -m paper_2603_08343_amd.profiling summarize --workload C5_large \
-                     --kernel-stats OUT/kt/kt_kernel_stats.csv --pmc OUT/*/*_counter_collection.csv
+                     --kernel-stats OUT/kt/kt_kernel_stats.csv --kernel-trace OUT/kt/kt_kernel_trace.csv \
+                     --pmc OUT/*/*_counter_collection.csv
 
 Nothing here is on the product path.
 """
@@ -74,6 +75,21 @@ def summarize(args):
             if "wht::" in row["Name"]:
                 out.append(f"  {_short(row['Name']):48s} calls {row['Calls']:>5s}  avg {float(row['AverageNs']):10.0f}"
                            f"  min {row['MinNs']:>8s}  max {row['MaxNs']:>8s}  {row['Percentage']}%")
+
+    if args.kernel_trace:
+        # the benchmark's timed region is its last `--last` steps: the launches before it are the
+        # untimed warm-up, during which the clocks are still settling
+        per_kernel = collections.defaultdict(list)
+        for row in csv.DictReader(open(args.kernel_trace)):
+            if "wht::" in row["Kernel_Name"]:
+                per_kernel[_short(row["Kernel_Name"])].append(
+                    (int(row["Start_Timestamp"]), int(row["End_Timestamp"]) - int(row["Start_Timestamp"])))
+        out.append("")
+        out.append(f"kernel-trace, last {args.last} launches of each kernel (the benchmark's timed region), ns:")
+        for k, launches in sorted(per_kernel.items()):
+            tail = [d for _, d in sorted(launches)[-args.last:]]
+            out.append(f"  {k:48s} calls {len(tail):>5d}  avg {sum(tail) / len(tail):10.0f}"
+                       f"  min {min(tail):>8d}  max {max(tail):>8d}")
 
     counters = collections.defaultdict(lambda: collections.defaultdict(list))
     durations = collections.defaultdict(list)
@@ -146,6 +162,8 @@ def main():
     s = sub.add_parser("summarize")
     s.add_argument("--workload", default="C5_large")
     s.add_argument("--kernel-stats")
+    s.add_argument("--kernel-trace", help="kt_kernel_trace.csv of the same run")
+    s.add_argument("--last", type=int, default=100, help="launches per kernel in the timed region")
     s.add_argument("--pmc", nargs="*")
     s.add_argument("--out")
     s.set_defaults(fn=summarize)
