@@ -121,3 +121,39 @@ def test_product_path_never_imports_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text, f
                 assert "wht_oracle" not in text, f
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    """include/wht_affine.h must be usable from C (no C++ in the signatures): compile a C99
+    translation unit that takes the address of every declared function with the declared
+    prototype, link it against the built library, and run it (no GPU call is made)."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "wht_affine.h"
+int main(void) {
+    int (*fwd)(const void *, const float *, const float *, void *, int64_t, int32_t, int32_t, void *) = wht_affine_forward;
+    int (*fwdr)(const void *, const float *, const float *, const void *, void *, int64_t, int32_t, int32_t, void *) = wht_affine_forward_residual;
+    size_t (*wsq)(int64_t, int32_t, int32_t) = wht_affine_backward_workspace_bytes;
+    int (*bwd)(const void *, const void *, const float *, void *, float *, float *, int64_t, int32_t, int32_t,
+               void *, size_t, void *) = wht_affine_backward;
+    /* argument validation happens before anything touches the GPU */
+    if (fwd(NULL, NULL, NULL, NULL, 4, 256, WHT_DTYPE_F32, NULL) != WHT_ERR_NULL_PTR) return 1;
+    if (fwdr((void *)16, (float *)16, (float *)16, (void *)16, (void *)16, 4, 100, WHT_DTYPE_BF16, NULL) != WHT_ERR_BAD_DIM) return 2;
+    if (wsq(0, 1024, WHT_DTYPE_BF16) != 0) return 3;
+    if (bwd((void *)16, (void *)16, (float *)16, (void *)16, (float *)16, (float *)16, 4, 1024, 7, NULL, 0, NULL)
+        != WHT_ERR_BAD_DTYPE) return 4;
+    if (WHT_MIN_D != 32 || WHT_MAX_D != 16384 || WHT_MIN_D_TWELVE != 768 || WHT_MAX_D_TWELVE != 6144) return 5;
+    printf("%s|%d\n", wht_affine_status_string(WHT_OK), wht_affine_version());
+    return 0;
+}
+''')
+    exe = tmp_path / "use_header"
+    libdir = os.path.dirname(binding.library_path())
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic",
+                    "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src),
+                    "-L", libdir, "-l:libwht_affine.so", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, (out.returncode, out.stderr)
+    assert out.stdout.strip().startswith("ok|")
