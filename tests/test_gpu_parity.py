@@ -324,6 +324,65 @@ def test_in_place_and_preallocated_outputs():
     assert torch.equal(da2, da_ref) and torch.equal(db2, db_ref)
 
 
+@pytest.mark.parametrize("d,N", [(4096, 16), (8192, 70), (1536, 33), (256, 40)])
+def test_hip_graph_replays_match_eager(d, N):
+    """Forward, fused-residual forward and backward captured once into a HIP graph and replayed with
+    new inputs each time (the buffers are rewritten in place between replays, with the program's own
+    eager work and synchronisations in between): every replay must equal the eager result bit for
+    bit, and the first replay's result must equal the oracle's."""
+    _announce(f"graph replay d={d} N={N}")
+    a = torch.from_numpy(synth.make_inputs(1, d, "bf16", seed=1).alpha).cuda()
+    b = torch.from_numpy(synth.make_inputs(1, d, "bf16", seed=1).beta).cuda()
+    x = torch.empty(N, d, device="cuda", dtype=torch.bfloat16)
+    dy, resid = torch.empty_like(x), torch.empty_like(x)
+    y, yr, dx = torch.empty_like(x), torch.empty_like(x), torch.empty_like(x)
+    da, db = torch.empty(d, device="cuda"), torch.empty(d, device="cuda")
+    ws = torch.empty(max(16, wht.wht_affine_backward_workspace_bytes(N, d, wht.DTYPE_BF16)),
+                     dtype=torch.uint8, device="cuda")
+
+    def step():
+        wht.wht_affine_forward(x, a, b, y=y)
+        wht.wht_affine_forward_residual(x, a, b, resid, y=yr)
+        wht.wht_affine_backward(dy, x, a, dx=dx, dalpha=da, dbeta=db, workspace=ws)
+
+    def load(seed):
+        inp = synth.make_inputs(N, d, "bf16", seed=seed)
+        x.copy_(to_gpu(inp.x, "bf16"))
+        dy.copy_(to_gpu(inp.dy, "bf16"))
+        resid.copy_(to_gpu(synth.make_inputs(N, d, "bf16", seed=seed + 100).x, "bf16"))
+        return inp
+
+    load(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                        # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for replay, seed in enumerate((21, 22, 23, 24)):
+        inp = load(seed)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (y, yr, dx, da, db)]
+        for t in (y, yr, dx, da, db):
+            t.zero_()
+        step()                                        # eager, same buffers
+        torch.cuda.synchronize()
+        for name, g, e in zip(("y", "y+resid", "dx", "dalpha", "dbeta"), got, (y, yr, dx, da, db)):
+            view = torch.int16 if g.dtype == torch.bfloat16 else torch.int32
+            assert torch.equal(g.view(view), e.view(view)), f"replay {replay}: {name} differs from eager"
+        if replay == 0:
+            assert_io_close(got[0], oracle.forward(inp.x, inp.alpha * 0 + a.cpu().numpy(), b.cpu().numpy(), "fast"),
+                            "bf16", "graph y")
+            rdx, rda, rdb = oracle.backward(inp.dy, inp.x, a.cpu().numpy(), "fast")
+            assert_io_close(got[2], rdx, "bf16", "graph dx")
+            assert_grad_close(got[3], rda, "graph dalpha")
+            assert_grad_close(got[4], rdb, "graph dbeta")
+
+
 def test_backward_is_bit_reproducible():
     inp = synth.make_inputs(4099, 1024, "bf16", seed=13)
     first = run_backward(inp)
