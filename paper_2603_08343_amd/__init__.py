@@ -2,7 +2,8 @@
 
 All arithmetic runs in the HIP kernels of libwht_affine.so (C ABI in include/wht_affine.h); this
 package only marshals arguments.  There is no CPU fallback: without the built library, or without a
-GPU, the calls raise.
+GPU, the calls raise.  `autograd` (imported on demand: it needs torch) wraps the entry points in a
+torch.autograd.Function and a Module.
 """
 from .binding import (  # noqa: F401
     DTYPE_BF16,

@@ -383,6 +383,41 @@ def test_hip_graph_replays_match_eager(d, N):
             assert_grad_close(got[4], rdb, "graph dbeta")
 
 
+@pytest.mark.parametrize("d,dtype", [(1024, "bf16"), (768, "bf16"), (256, "f32")])
+def test_autograd_module_matches_oracle(d, dtype):
+    """The autograd wrapper only routes tensors: a [B, S, d] activation through the Module, a loss
+    whose gradient with respect to y is a given dy, and .backward() must reproduce the oracle's
+    y, dx, dalpha, dbeta (and pass dy through to the residual stream)."""
+    from paper_2603_08343_amd.autograd import WhtAffine
+    B, S = 3, 11
+    inp = synth.make_inputs(B * S, d, dtype, seed=31)
+    _announce(f"autograd d={d} {dtype}")
+    layer = WhtAffine(d, device="cuda")
+    with torch.no_grad():
+        layer.alpha.copy_(torch.from_numpy(inp.alpha))
+        layer.beta.copy_(torch.from_numpy(inp.beta))
+    x = to_gpu(inp.x, dtype).view(B, S, d).requires_grad_(True)
+    resid = to_gpu(synth.make_inputs(B * S, d, dtype, seed=32).x, dtype).view(B, S, d).requires_grad_(True)
+    dy = to_gpu(inp.dy, dtype).view(B, S, d)
+    y = layer(x, resid)
+    assert y.shape == (B, S, d) and y.dtype == x.dtype
+    y.backward(dy)
+    torch.cuda.synchronize()
+    rin = synth.make_inputs(B * S, d, dtype, seed=32).x
+    assert_io_close(y.detach().view(B * S, d), oracle.forward_residual(inp.x, inp.alpha, inp.beta, rin, _method(d)),
+                    dtype, "module y")
+    rdx, rda, rdb = oracle.backward(inp.dy, inp.x, inp.alpha, _method(d))
+    assert_io_close(x.grad.view(B * S, d), rdx, dtype, "module dx")
+    assert_grad_close(layer.alpha.grad, rda, "module dalpha")
+    assert_grad_close(layer.beta.grad, rdb, "module dbeta")
+    view = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(resid.grad.view(view), dy.view(view))
+    # without the residual stream
+    x2 = to_gpu(inp.x, dtype).view(B, S, d)
+    assert_io_close(layer(x2).detach().view(B * S, d), oracle.forward(inp.x, inp.alpha, inp.beta, _method(d)),
+                    dtype, "module y (no residual)")
+
+
 def test_backward_is_bit_reproducible():
     inp = synth.make_inputs(4099, 1024, "bf16", seed=13)
     first = run_backward(inp)

@@ -157,3 +157,15 @@ int main(void) {
     out = subprocess.run([str(exe)], capture_output=True, text=True)
     assert out.returncode == 0, (out.returncode, out.stderr)
     assert out.stdout.strip().startswith("ok|")
+
+
+def test_autograd_wrapper_has_no_cpu_path():
+    """The Module builds on the CPU (parameters only) but refuses to run there."""
+    import torch
+    from paper_2603_08343_amd.autograd import WhtAffine
+    layer = WhtAffine(64)
+    assert layer.alpha.dtype == torch.float32 and float(layer.alpha.detach().sum()) == 64.0
+    assert float(layer.beta.detach().abs().sum()) == 0.0
+    if not torch.cuda.is_available():
+        with pytest.raises((RuntimeError, ValueError)):
+            layer(torch.zeros(2, 64))
