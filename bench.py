@@ -304,6 +304,72 @@ def graph_replay_step(torch, b, steps):
         return {"note": f"graph replay not measured: {type(exc).__name__}: {exc}"[:200]}
 
 
+def attention_block_context(torch, wht, iters=20):
+    """The layer where the paper uses it: one attention block (QKV projection, causal attention, output
+    layer, residual add) at the paper's four model widths (Table 2) and its two inference shapes
+    (prefill: batch 1024 x 64 tokens; decode: batch 2048, one new token against a 128-token cache),
+    forward, bf16, random weights.  Everything but the output layer is stock torch (hipBLASLt GEMM,
+    scaled_dot_product_attention) and identical in both variants; the output layer is either the
+    dense W_O (addmm with the residual as its additive input) or wht_affine_forward_residual."""
+    import torch.nn.functional as F
+    rows = []
+    g = torch.Generator(device="cuda").manual_seed(0)
+    for size, d, heads in (("Tiny", 768, 12), ("Small", 1024, 16), ("Base", 1536, 16), ("Large", 2048, 16)):
+        dh = d // heads
+        wqkv = (torch.randn(3 * d, d, device="cuda", generator=g) / d ** 0.5).to(torch.bfloat16)
+        wo = (torch.randn(d, d, device="cuda", generator=g) / d ** 0.5).to(torch.bfloat16)
+        alpha = torch.rand(d, device="cuda", generator=g) + 0.5
+        beta = 0.02 * torch.randn(d, device="cuda", generator=g)
+        for phase, B, T, L in (("prefill", 1024, 64, 64), ("decode", 2048, 1, 128)):
+            x = torch.randn(B, T, d, device="cuda", generator=g).to(torch.bfloat16)
+            kc = torch.randn(B, heads, L, dh, device="cuda", generator=g).to(torch.bfloat16)
+            vc = torch.randn(B, heads, L, dh, device="cuda", generator=g).to(torch.bfloat16)
+            resid = x.view(B * T, d)
+            out = torch.empty(B * T, d, device="cuda", dtype=torch.bfloat16)
+
+            def heads_out():
+                qkv = F.linear(x, wqkv).view(B, T, 3, heads, dh)
+                q = qkv[:, :, 0].transpose(1, 2)
+                if phase == "prefill":
+                    k, v = qkv[:, :, 1].transpose(1, 2), qkv[:, :, 2].transpose(1, 2)
+                    o = F.scaled_dot_product_attention(q, k, v, is_causal=True)
+                else:
+                    o = F.scaled_dot_product_attention(q, kc, vc)
+                return o.transpose(1, 2).reshape(B * T, d)
+
+            def dense_block():
+                return torch.addmm(resid, heads_out(), wo.t())
+
+            def wht_block():
+                return wht.wht_affine_forward_residual(heads_out(), alpha, beta, resid, y=out)
+
+            ho = heads_out()
+
+            def timeit(fn):
+                for _ in range(5):
+                    fn()
+                a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                a.record()
+                for _ in range(iters):
+                    fn()
+                e.record()
+                torch.cuda.synchronize()
+                return a.elapsed_time(e) / iters
+
+            row = {"size": size, "d_model": d, "heads": heads, "phase": phase, "tokens": B * T,
+                   "block_dense_ms": timeit(dense_block), "block_wht_ms": timeit(wht_block),
+                   "output_layer_dense_ms": timeit(lambda: torch.addmm(resid, ho, wo.t())),
+                   "output_layer_wht_ms": timeit(lambda: wht.wht_affine_forward_residual(ho, alpha, beta, resid, y=out))}
+            row["block_speedup"] = row["block_dense_ms"] / row["block_wht_ms"]
+            row["output_layer_speedup"] = row["output_layer_dense_ms"] / row["output_layer_wht_ms"]
+            rows.append(row)
+            del x, kc, vc, out, ho
+        del wqkv, wo
+        torch.cuda.empty_cache()
+    return rows
+
+
 def fused_residual(torch, wht, synth, name, steps=100, warmup=100):
     """y = resid + alpha (.) Hx + beta in one kernel (3 N d s bytes) against the unfused pair:
     the layer's forward followed by torch's in-place add on the residual stream (5 N d s bytes)."""
@@ -419,6 +485,10 @@ def main():
             torch.cuda.empty_cache()
         extras["fused_residual_forward"] = [fused_residual(torch, wht, synth, n) for n in ("C5_large", "C4b_roofline")]
         extras["headline_step_graph_replay"] = graph_step
+        try:
+            extras["attention_block_context"] = attention_block_context(torch, wht)
+        except Exception as exc:                      # stock-torch harness around the layer: optional
+            extras["attention_block_context"] = {"note": f"not measured: {type(exc).__name__}: {exc}"[:200]}
         extras["decode"] = decode_latency(torch, wht, synth)
         extras["dense_wo_same_shape"] = dense_wo(torch, w)
         extras["dense_wo_same_shape"]["workload"] = w.name
