@@ -118,6 +118,13 @@ size_t wht_affine_backward_workspace_bytes(int64_t N, int32_t d, int32_t dtype);
  *   workspace    device scratch, 16-byte aligned, at least ..._workspace_bytes(N, d, dtype) bytes;
  *                contents on entry are ignored, contents on return are unspecified
  * The reduction over tokens has a fixed order: results are bit-reproducible run to run.
+ *
+ * Outputs may be left out:
+ *   dalpha = dbeta = NULL   only dx is computed (frozen parameters).  x and workspace are then not
+ *                           used and may be NULL; the call moves the bytes of a forward pass.
+ *   dx = NULL               only dalpha and dbeta are computed.
+ * dalpha and dbeta come together: exactly one of them NULL, or all three outputs NULL, is
+ * WHT_ERR_NULL_PTR.  The values of the outputs that are computed do not depend on which others are.
  */
 int wht_affine_backward(const void *dy, const void *x, const float *alpha,
                         void *dx, float *dalpha, float *dbeta,

@@ -37,9 +37,15 @@ class WhtAffineFunction(torch.autograd.Function):
         dy2 = dy.reshape(-1, d)
         if not dy2.is_contiguous():
             dy2 = dy2.contiguous()
-        dx, dalpha, dbeta = binding.wht_affine_backward(dy2, x2, alpha)
+        want_dx = ctx.needs_input_grad[0]
+        want_pg = ctx.needs_input_grad[1] or ctx.needs_input_grad[2]
+        dx = dalpha = dbeta = None
+        if want_dx or want_pg:
+            dx, dalpha, dbeta = binding.wht_affine_backward(dy2, x2, alpha, want_dx=want_dx,
+                                                            want_param_grads=want_pg)
         # the residual stream's gradient is dy itself
-        return dx.view(dy.shape), dalpha, dbeta, (dy if ctx.has_resid else None)
+        return (dx.view(dy.shape) if dx is not None else None, dalpha, dbeta,
+                dy if ctx.has_resid and ctx.needs_input_grad[3] else None)
 
 
 def wht_affine(x, alpha, beta, resid=None):

@@ -169,42 +169,58 @@ def wht_affine_forward_residual(x, alpha, beta, resid, y=None, stream=None):
     return y
 
 
-def wht_affine_backward(dy, x, alpha, dx=None, dalpha=None, dbeta=None, workspace=None, stream=None):
-    """Returns (dx, dalpha, dbeta) with dx = H(alpha (.) dy), dalpha = sum_n dy (.) Hx, dbeta = sum_n dy."""
+def wht_affine_backward(dy, x, alpha, dx=None, dalpha=None, dbeta=None, workspace=None, stream=None,
+                        want_dx=True, want_param_grads=True):
+    """Returns (dx, dalpha, dbeta) with dx = H(alpha (.) dy), dalpha = sum_n dy (.) Hx, dbeta = sum_n dy.
+    want_dx=False or want_param_grads=False leaves those outputs out (None in the result); without
+    the parameter gradients x is not needed and may be None."""
     torch = _torch()
-    _check_io(x, "x", torch)
-    _check_io(dy, "dy", torch, like=x)
-    N, d = x.shape
-    _check_param(alpha, "alpha", d, x, torch)
-    code = _dtype_code(x, torch)
-    if dx is None:
-        dx = torch.empty_like(x)
+    if not want_dx and not want_param_grads:
+        raise ValueError("nothing to compute: want_dx and want_param_grads are both False")
+    _check_io(dy, "dy", torch)
+    if want_param_grads or x is not None:
+        _check_io(x, "x", torch, like=dy)
+    N, d = dy.shape
+    _check_param(alpha, "alpha", d, dy, torch)
+    code = _dtype_code(dy, torch)
+    if not want_dx:
+        dx = None
+    elif dx is None:
+        dx = torch.empty_like(dy)
     else:
-        _check_io(dx, "dx", torch, like=x)
-    if dalpha is None:
-        dalpha = torch.empty(d, dtype=torch.float32, device=x.device)
+        _check_io(dx, "dx", torch, like=dy)
+    if not want_param_grads:
+        dalpha = dbeta = None
     else:
-        _check_param(dalpha, "dalpha", d, x, torch)
-    if dbeta is None:
-        dbeta = torch.empty(d, dtype=torch.float32, device=x.device)
-    else:
-        _check_param(dbeta, "dbeta", d, x, torch)
-    need = wht_affine_backward_workspace_bytes(N, d, code)
-    if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
-    elif not workspace.is_cuda or not workspace.is_contiguous() or workspace.device != x.device:
-        raise ValueError("workspace must be a contiguous GPU tensor on x's device")
-    ws_bytes = workspace.numel() * workspace.element_size()
-    io = (dy.data_ptr(), x.data_ptr(), dx.data_ptr()) if N > 0 else (alpha.data_ptr(),) * 3
-    with torch.cuda.device(x.device):
-        rc = wht_affine_backward_raw(io[0], io[1], alpha.data_ptr(), io[2],
-                                     dalpha.data_ptr(), dbeta.data_ptr(), N, d, code,
-                                     workspace.data_ptr(), ws_bytes,
-                                     _stream_handle(stream, torch, x.device))
+        if dalpha is None:
+            dalpha = torch.empty(d, dtype=torch.float32, device=dy.device)
+        else:
+            _check_param(dalpha, "dalpha", d, dy, torch)
+        if dbeta is None:
+            dbeta = torch.empty(d, dtype=torch.float32, device=dy.device)
+        else:
+            _check_param(dbeta, "dbeta", d, dy, torch)
+    ws_ptr, ws_bytes = 0, 0
+    if want_param_grads:
+        need = wht_affine_backward_workspace_bytes(N, d, code)
+        if workspace is None:
+            workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dy.device)
+        elif not workspace.is_cuda or not workspace.is_contiguous() or workspace.device != dy.device:
+            raise ValueError("workspace must be a contiguous GPU tensor on dy's device")
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    # torch gives an empty tensor a NULL address; the library never touches dy, x, dx when N = 0
+    dummy = alpha.data_ptr()
+    dy_p = dy.data_ptr() if N > 0 else dummy
+    x_p = 0 if not want_param_grads else (x.data_ptr() if N > 0 else dummy)
+    dx_p = 0 if dx is None else (dx.data_ptr() if N > 0 else dummy)
+    with torch.cuda.device(dy.device):
+        rc = wht_affine_backward_raw(dy_p, x_p, alpha.data_ptr(), dx_p,
+                                     dalpha.data_ptr() if dalpha is not None else 0,
+                                     dbeta.data_ptr() if dbeta is not None else 0, N, d, code,
+                                     ws_ptr, ws_bytes, _stream_handle(stream, torch, dy.device))
     if rc != 0:
         raise WhtAffineError(rc, "wht_affine_backward")
     return dx, dalpha, dbeta
-
 
 def wht_affine_copy_baseline(src, dst, stream=None):
     """dst <- src with the kernels' access pattern (measurement aid)."""

@@ -66,11 +66,23 @@ template <class C>
 static int launch_backward(const void* dy, const void* x, const float* alpha, void* dx, float* dalpha,
                            float* dbeta, int64_t N, void* workspace, hipStream_t stream) {
     using T = typename C::io::elem_t;
-    const int grid = grid_for<C>(N, true);
-    hipLaunchKernelGGL(backward_kernel<C>, dim3(grid), dim3(C::BT), 0, stream,
-                       static_cast<const T*>(dy), static_cast<const T*>(x), alpha, static_cast<T*>(dx),
-                       static_cast<float*>(workspace), N);
+    const bool grads = dalpha != nullptr;
+    const int grid = grid_for<C>(N, grads);      // dx alone streams like a forward pass
+
+    if (grads && dx)
+        hipLaunchKernelGGL((backward_kernel<C, true, true>), dim3(grid), dim3(C::BT), 0, stream,
+                           static_cast<const T*>(dy), static_cast<const T*>(x), alpha, static_cast<T*>(dx),
+                           static_cast<float*>(workspace), N);
+    else if (grads)
+        hipLaunchKernelGGL((backward_kernel<C, true, false>), dim3(grid), dim3(C::BT), 0, stream,
+                           static_cast<const T*>(dy), static_cast<const T*>(x), alpha, static_cast<T*>(nullptr),
+                           static_cast<float*>(workspace), N);
+    else
+        hipLaunchKernelGGL((backward_kernel<C, false, true>), dim3(grid), dim3(C::BT), 0, stream,
+                           static_cast<const T*>(dy), static_cast<const T*>(nullptr), alpha, static_cast<T*>(dx),
+                           static_cast<float*>(nullptr), N);
     if (hipGetLastError() != hipSuccess) return WHT_ERR_LAUNCH;
+    if (!grads) return WHT_OK;
     if constexpr (C::kRow >= 4096)
         hipLaunchKernelGGL(reduce_partials_kernel<16>, dim3((C::kRow + 63) / 64, 2), dim3(1024), 0, stream,
                            static_cast<const float*>(workspace), grid, C::kRow, dalpha, dbeta);
@@ -234,7 +246,10 @@ int wht_affine_backward(const void* dy, const void* x, const float* alpha, void*
                         float* dbeta, int64_t N, int32_t d, int32_t dtype, void* workspace,
                         size_t workspace_bytes, void* stream) {
     using namespace wht;
-    if (!dy || !x || !alpha || !dx || !dalpha || !dbeta) return WHT_ERR_NULL_PTR;
+    const bool grads = dalpha != nullptr || dbeta != nullptr;
+    if (!dy || !alpha) return WHT_ERR_NULL_PTR;
+    if (grads && (!dalpha || !dbeta || !x)) return WHT_ERR_NULL_PTR;   // the two sums come together
+    if (!grads && !dx) return WHT_ERR_NULL_PTR;                        // nothing asked for
     Width w{};
     if (int rc = check_dims(N, d, dtype, &w)) return rc;
     if (!aligned16(dy) || !aligned16(x) || !aligned16(alpha) || !aligned16(dx) || !aligned16(dalpha) ||
@@ -242,12 +257,15 @@ int wht_affine_backward(const void* dy, const void* x, const float* alpha, void*
         return WHT_ERR_MISALIGNED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (N == 0) {
+        if (!grads) return WHT_OK;
         hipLaunchKernelGGL(zero_kernel, dim3((d + 255) / 256), dim3(256), 0, s, dalpha, dbeta, d);
         return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
     }
-    const size_t need = wht_affine_backward_workspace_bytes(N, d, dtype);
-    if (!workspace || workspace_bytes < need) return WHT_ERR_WORKSPACE;
-    if (!aligned16(workspace)) return WHT_ERR_MISALIGNED;
+    if (grads) {
+        const size_t need = wht_affine_backward_workspace_bytes(N, d, dtype);
+        if (!workspace || workspace_bytes < need) return WHT_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return WHT_ERR_MISALIGNED;
+    }
     Args a{};
     a.dy = dy; a.x = x; a.alpha = alpha; a.dx = dx; a.dalpha = dalpha; a.dbeta = dbeta; a.N = N;
     a.workspace = workspace; a.stream = s;

@@ -578,10 +578,10 @@ __device__ __forceinline__ void transform_from_raw(float (&r)[C::E], const uint4
 }
 
 // registers in the last layout -> H_raw (.) in the first layout.
-template <class C>
+template <class C, bool TRAILING_BARRIER = false>
 __device__ __forceinline__ void transform_back(float (&r)[C::E], float* lds, const ThreadMap<C>& tm,
                                                const HadamardB& b, const HadamardB& b2) {
-    transform<C, false, false>(r, lds, tm);
+    transform<C, false, TRAILING_BARRIER>(r, lds, tm);
     if constexpr (C::kMfma) mfma_rounds_from_f32<C>(r, b, b2);
 }
 
@@ -699,17 +699,23 @@ __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::el
 //   g = alpha' dy;  transform back;  wait for everything pending;  store dx(k).
 // As in the forward kernel the single wait precedes the stores and only covers loads issued a whole
 // iteration earlier (and the previous token's stores).
-template <class C>
+//
+// GRADS / DX select the outputs: without GRADS x is never read and no sums are kept (dx only, the
+// traffic of a forward pass); without DX nothing is transformed back or stored.  With only one of
+// the two, consecutive transforms run in the same order and need the trailing barrier again.
+template <class C, bool GRADS, bool DX>
 __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::elem_t* dy,
                                                          const typename C::io::elem_t* x,
                                                          const float* __restrict__ alpha,
                                                          typename C::io::elem_t* dx,
                                                          float* __restrict__ partials,   // [grid][2][kRow]
                                                          int64_t N) {
+    static_assert(GRADS || DX, "nothing to compute");
     __shared__ __align__(16) float lds[C::kExchangeBytes / 4];
-    __shared__ __align__(16) unsigned char stage_x_buf[C::kStageBytes];
+    __shared__ __align__(16) unsigned char stage_x_buf[GRADS ? C::kStageBytes : 16];
     __shared__ __align__(16) unsigned char stage_g_buf[C::kStageBytes];
     constexpr int LAST = C::P - 1;
+    constexpr bool BOTH = GRADS && DX;
     const unsigned t = threadIdx.x % C::TPT;
     Walker<C> wk{N, (N + C::G - 1) / C::G, threadIdx.x / C::TPT};
     ThreadMap<C> tm;
@@ -718,54 +724,72 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
     if constexpr (C::kMfma) hb = make_hadamard_b();
     if constexpr (C::kTwelve) hbp = make_paley_b(hb);
     const HadamardB& hb2 = C::kTwelve ? hbp : hb;
-    unsigned char* stage_x = stage_x_buf + (threadIdx.x >> 6) * (C::NV * 1024);
+    unsigned char* stage_x = stage_x_buf + (GRADS ? (threadIdx.x >> 6) * (C::NV * 1024) : 0);
     unsigned char* stage_g = stage_g_buf + (threadIdx.x >> 6) * (C::NV * 1024);
 
     const int64_t step = gridDim.x;
     int64_t grp = blockIdx.x;
     if (grp < wk.groups) {
-        stage_issue<C, 0>(stage_x, x + wk.row(grp) * C::kRow, tm.first_elem, tm.first_ok);
+        if constexpr (GRADS) stage_issue<C, 0>(stage_x, x + wk.row(grp) * C::kRow, tm.first_elem, tm.first_ok);
         stage_issue<C, LAST>(stage_g, dy + wk.row(grp) * C::kRow, tm.last_elem, tm.last_ok);
     }
 
-    float a[C::E], da[C::E], db[C::E];
-    param_get<C, LAST>(a, alpha, tm.last_elem, tm.last_ok, inv_sqrt_d<C>());
+    float a[DX ? C::E : 1], da[GRADS ? C::E : 1], db[GRADS ? C::E : 1];
+    if constexpr (DX) param_get<C, LAST>(a, alpha, tm.last_elem, tm.last_ok, inv_sqrt_d<C>());
+    if constexpr (GRADS) {
 #pragma unroll
-    for (int i = 0; i < C::E; ++i) { da[i] = 0.0f; db[i] = 0.0f; }
+        for (int i = 0; i < C::E; ++i) { da[i] = 0.0f; db[i] = 0.0f; }
+    }
     wait_vmem<0>();
     for (; grp < wk.groups; grp += step) {
         const bool more = grp + step < wk.groups;
-        uint4 raw[C::NV], graw[C::NV];
-        stage_read<C>(raw, stage_x);
+        uint4 raw[GRADS ? C::NV : 1], graw[C::NV];
+        if constexpr (GRADS) {
+            stage_read<C>(raw, stage_x);
+            zero_padding<C>(raw, tm.first_ok);
+        }
         stage_read<C>(graw, stage_g);
-        zero_padding<C>(raw, tm.first_ok);
         zero_padding<C>(graw, tm.last_ok);
         if (more) {
-            stage_issue<C, 0>(stage_x, x + wk.row(grp + step) * C::kRow, tm.first_elem, tm.first_ok);
+            if constexpr (GRADS)
+                stage_issue<C, 0>(stage_x, x + wk.row(grp + step) * C::kRow, tm.first_elem, tm.first_ok);
             stage_issue<C, LAST>(stage_g, dy + wk.row(grp + step) * C::kRow, tm.last_elem, tm.last_ok);
         }
-        float r[C::E], g[C::E];
-        transform_from_raw<C, false>(r, raw, lds, tm, hb, hb2);   // r = H_raw x, last layout
-        unpack_all<C>(g, graw);
+        float g[C::E];
         const int64_t tok = wk.token(grp);
         const bool active = C::G == 1 || tok < N;             // one slot per workgroup: never ragged
-        if constexpr (C::G > 1) {
-            if (!active) {                                    // ragged last group: contribute nothing
+        auto take_dy = [&]() {
+            unpack_all<C>(g, graw);
+            if constexpr (C::G > 1) {
+                if (!active) {                                // ragged last group: contribute nothing
 #pragma unroll
-                for (int i = 0; i < C::E; ++i) g[i] = 0.0f;
+                    for (int i = 0; i < C::E; ++i) g[i] = 0.0f;
+                }
             }
-        }
+        };
+        if constexpr (GRADS) {
+            float r[C::E];
+            transform_from_raw<C, !BOTH>(r, raw, lds, tm, hb, hb2);   // r = H_raw x, last layout
+            take_dy();
 #pragma unroll
-        for (int i = 0; i < C::E; ++i) {
-            da[i] = fmaf(g[i], r[i], da[i]);                  // 1/sqrt d applied once at the end
-            db[i] += g[i];
-            g[i] *= a[i];
+            for (int i = 0; i < C::E; ++i) {
+                da[i] = fmaf(g[i], r[i], da[i]);              // 1/sqrt d applied once at the end
+                db[i] += g[i];
+            }
+        } else {
+            take_dy();
         }
-        transform_back<C>(g, lds, tm, hb, hb2);               // g = H_raw(alpha' dy), first layout
-        if (more) wait_vmem<0>();
-        global_put<C, 0>(g, dx + tok * C::kRow, tm.first_elem, active && tm.first_ok);
+        if constexpr (DX) {
+#pragma unroll
+            for (int i = 0; i < C::E; ++i) g[i] *= a[i];
+            transform_back<C, !BOTH>(g, lds, tm, hb, hb2);    // g = H_raw(alpha' dy), first layout
+            if (more) wait_vmem<0>();
+            global_put<C, 0>(g, dx + tok * C::kRow, tm.first_elem, active && tm.first_ok);
+        } else {
+            if (more) wait_vmem<0>();
+        }
     }
-
+    if constexpr (GRADS) {
     // Sum the G token slots of this workgroup through LDS, then write the workgroup's row.
     if constexpr (C::G > 1) __syncthreads();      // the last exchange's reads are done everywhere
     const float s = inv_sqrt_d<C>();
@@ -794,6 +818,7 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
             __syncthreads();
         }
     }
+    }   // GRADS
 }
 
 // out[which][j] = sum over rows of partials[row][which][j].  Workgroup = CG float4 columns x

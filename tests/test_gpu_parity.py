@@ -418,6 +418,48 @@ def test_autograd_module_matches_oracle(d, dtype):
                     dtype, "module y (no residual)")
 
 
+@pytest.mark.parametrize("d,dtype,N", [(64, "f32", 70), (512, "bf16", 131), (1024, "bf16", 263), (4096, "bf16", 35),
+                                       (8192, "bf16", 129), (768, "bf16", 67), (6144, "bf16", 9), (8192, "f32", 9)])
+def test_backward_with_outputs_left_out(d, dtype, N):
+    """dx alone (frozen parameters) and the parameter gradients alone: the values must be those of
+    the full call, bit for bit, and hence the oracle's."""
+    _announce(f"backward, optional outputs d={d} {dtype} N={N}")
+    inp = synth.make_inputs(N, d, dtype, seed=d + 3)
+    x, dy = to_gpu(inp.x, dtype), to_gpu(inp.dy, dtype)
+    a = torch.from_numpy(inp.alpha).cuda()
+    dx, da, db = wht.wht_affine_backward(dy, x, a)
+    dx_only, none_a, none_b = wht.wht_affine_backward(dy, None, a, want_param_grads=False)
+    none_x, da_only, db_only = wht.wht_affine_backward(dy, x, a, want_dx=False)
+    torch.cuda.synchronize()
+    assert none_a is None and none_b is None and none_x is None
+    view = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(dx_only.view(view), dx.view(view))
+    assert torch.equal(da_only, da) and torch.equal(db_only, db)
+    rdx, rda, rdb = oracle.backward(inp.dy, inp.x, inp.alpha, _method(d))
+    assert_io_close(dx_only, rdx, dtype, "dx alone")
+    assert_grad_close(da_only, rda, "dalpha alone")
+    assert_grad_close(db_only, rdb, "dbeta alone")
+    with pytest.raises(ValueError):
+        wht.wht_affine_backward(dy, x, a, want_dx=False, want_param_grads=False)
+
+
+def test_autograd_frozen_parameters_take_the_dx_only_path():
+    from paper_2603_08343_amd.autograd import WhtAffine
+    d, N = 2048, 40
+    inp = synth.make_inputs(N, d, "bf16", seed=41)
+    layer = WhtAffine(d, device="cuda")
+    with torch.no_grad():
+        layer.alpha.copy_(torch.from_numpy(inp.alpha))
+    layer.alpha.requires_grad_(False)
+    layer.beta.requires_grad_(False)
+    x = to_gpu(inp.x, "bf16").requires_grad_(True)
+    layer(x).backward(to_gpu(inp.dy, "bf16"))
+    torch.cuda.synchronize()
+    assert layer.alpha.grad is None and layer.beta.grad is None
+    rdx, _, _ = oracle.backward(inp.dy, inp.x, inp.alpha, "fast", want_param_grads=False)
+    assert_io_close(x.grad, rdx, "bf16", "frozen-parameter dx")
+
+
 def test_backward_is_bit_reproducible():
     inp = synth.make_inputs(4099, 1024, "bf16", seed=13)
     first = run_backward(inp)

@@ -90,6 +90,13 @@ def test_backward_argument_validation():
     assert call(P, P, P, P, P, P, 100, 1024, 1, 0, ws) == WS
     assert call(P, P, P, P, P, P, 100, 1024, 1, P, ws - 1) == WS
     assert call(P, P, P, P, P, P, 100, 1024, 1, P + 4, ws) == ALIGN
+    # optional outputs: dalpha and dbeta come together; something must be asked for
+    assert call(P, P, P, P, P, 0, 100, 1024, 1, P, ws) == NULLP
+    assert call(P, P, P, 0, 0, 0, 100, 1024, 1, P, ws) == NULLP
+    assert call(P, 0, P, P, P, P, 100, 1024, 1, P, ws) == NULLP            # the sums need x
+    assert call(P, 0, P, P, 0, 0, 0, 1024, 1, 0, 0) == OK                  # dx only: no x, no workspace
+    assert call(P, 0, P, P + 8, 0, 0, 4, 1024, 1, 0, 0) == ALIGN
+    assert call(P, P, P, 0, P, P, 100, 1024, 1, 0, 0) == WS                # sums only still need it
 
 
 def test_workspace_query():
