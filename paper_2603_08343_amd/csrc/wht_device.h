@@ -128,7 +128,8 @@ struct Cfg {
 // (element bit 3, block) and applies  P12 (x) H_2  there; every other slot bit is an ordinary
 // Sylvester bit.  Bits 6 and 7 are lane bits in both memory layouts, so a slot's validity is a
 // property of the lane: lanes 24..31 and 56..63 of every wave sit out the loads and stores, and
-// the others move 64 contiguous bytes per block.
+// per instruction the others touch 64 contiguous bytes of every block, as two 32-byte lane pairs
+// (l, l+1) and (l+32, l+33).
 template <int LOGD, int LOGT, bool TWELVE = false>
 struct MfmaCfg {
     using io = IoBF16;
