@@ -12,7 +12,7 @@
  * stored: the kernels run the log2(d) add/subtract butterfly stages of Fig. 2.
  *
  * Widths d = 12 * 2^m.  The paper also trains d = 768 and d = 1536 (Table 2) and does not say which
- * matrix it uses there.  This library's reading, for bfloat16 tensors and d = 768 ... 6144:
+ * matrix it uses there.  This library's reading, for bfloat16 tensors and d = 768 ... 12288:
  *
  *     H_raw = P12 (x) S_{2^m}      H_raw[j][k] = P12[j / 2^m][k / 2^m] * (-1)^popcount(j & k & (2^m - 1))
  *
@@ -58,8 +58,8 @@ extern "C" {
 #define WHT_MIN_D 32
 #define WHT_MAX_D 16384        /* bfloat16 tensors */
 #define WHT_MAX_D_F32 8192     /* float32 tensors */
-#define WHT_MIN_D_TWELVE 768   /* d = 12 * 2^m, bfloat16 tensors: 768, 1536, 3072, 6144 */
-#define WHT_MAX_D_TWELVE 6144
+#define WHT_MIN_D_TWELVE 768   /* d = 12 * 2^m, bfloat16 tensors: 768, 1536, 3072, 6144, 12288 */
+#define WHT_MAX_D_TWELVE 12288
 
 typedef enum {
     WHT_DTYPE_F32  = 0,   /* x, y, dy, dx are IEEE binary32 */

@@ -221,15 +221,17 @@ int main(int argc, char** argv) {
     }
     bool ok = true;
     const bool verbose = argc > 1;
-    for (int n = 10; n <= 13; ++n) ok = check_twelve(n) && ok;
+    for (int n = 10; n <= 14; ++n) ok = check_twelve(n) && ok;
     for (int v : {2, 3})
         for (int n = 5; n <= (v == 2 ? 13 : 14); ++n) {
             const PlanDesc pl = make_plan(n, log_e_for(n, v), v);
             ok = check("butterfly", pl, v == 2 ? phys_pad2 : phys_pad3, lds_words_pad(1u << n, v), verbose) && ok;
         }
-    for (int n = 10; n <= 14; ++n) {
-        const PlanDesc pl = make_mfma_plan(n, mfma_log_tiles(n));
-        ok = check("mfma", pl, phys_rot, 1u << n, verbose) && ok;
-    }
+    for (int n = 10; n <= 14; ++n)
+        for (int backward = 0; backward < 2; ++backward) {
+            if (backward && mfma_log_tiles(n, true) == mfma_log_tiles(n, false)) continue;
+            const PlanDesc pl = make_mfma_plan(n, mfma_log_tiles(n, backward != 0));
+            ok = check("mfma", pl, phys_rot, 1u << n, verbose) && ok;
+        }
     return ok ? 0 : 1;
 }

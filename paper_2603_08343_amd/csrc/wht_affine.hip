@@ -104,13 +104,14 @@ struct Args {
     size_t workspace_out;
 };
 
-template <class C>
+// CF: configuration of the forward kernels, CB: of the backward kernels (and its workspace).
+template <class CF, class CB = CF>
 static int run(Op op, Args& a) {
     switch (op) {
-    case Op::Forward:  return launch_forward<C>(a.x, a.alpha, a.beta, a.resid, a.y, a.N, a.stream);
-    case Op::Backward: return launch_backward<C>(a.dy, a.x, a.alpha, a.dx, a.dalpha, a.dbeta, a.N,
-                                                 a.workspace, a.stream);
-    default:           a.workspace_out = workspace_for<C>(a.N); return WHT_OK;
+    case Op::Forward:  return launch_forward<CF>(a.x, a.alpha, a.beta, a.resid, a.y, a.N, a.stream);
+    case Op::Backward: return launch_backward<CB>(a.dy, a.x, a.alpha, a.dx, a.dalpha, a.dbeta, a.N,
+                                                  a.workspace, a.stream);
+    default:           a.workspace_out = workspace_for<CB>(a.N); return WHT_OK;
     }
 }
 
@@ -127,7 +128,8 @@ static bool use_mfma() {
 template <class Io, int LOGD>
 static int run_d(Op op, Args& a) {
     if constexpr (std::is_same<Io, IoBF16>::value && LOGD >= 10) {
-        if (use_mfma()) return run<MfmaCfg<LOGD, mfma_log_tiles(LOGD)>>(op, a);
+        if (use_mfma())
+            return run<MfmaCfg<LOGD, mfma_log_tiles(LOGD, false)>, MfmaCfg<LOGD, mfma_log_tiles(LOGD, true)>>(op, a);
     }
     return run<Cfg<LOGD, log_e_for(LOGD, Io::kLogVec), Io>>(op, a);
 }
@@ -154,10 +156,11 @@ static int dispatch_d(int logd, Op op, Args& a) {
 // Rows of 12 * 2^m elements (bfloat16): matrix-core schedule on 16 * 2^m slots.
 static int dispatch_twelve(int logslots, Op op, Args& a) {
     switch (logslots) {
-    case 10: return run<MfmaCfg<10, mfma_log_tiles(10), true>>(op, a);
-    case 11: return run<MfmaCfg<11, mfma_log_tiles(11), true>>(op, a);
-    case 12: return run<MfmaCfg<12, mfma_log_tiles(12), true>>(op, a);
-    case 13: return run<MfmaCfg<13, mfma_log_tiles(13), true>>(op, a);
+    case 10: return run<MfmaCfg<10, mfma_log_tiles(10, false), true>, MfmaCfg<10, mfma_log_tiles(10, true), true>>(op, a);
+    case 11: return run<MfmaCfg<11, mfma_log_tiles(11, false), true>, MfmaCfg<11, mfma_log_tiles(11, true), true>>(op, a);
+    case 12: return run<MfmaCfg<12, mfma_log_tiles(12, false), true>, MfmaCfg<12, mfma_log_tiles(12, true), true>>(op, a);
+    case 13: return run<MfmaCfg<13, mfma_log_tiles(13, false), true>, MfmaCfg<13, mfma_log_tiles(13, true), true>>(op, a);
+    case 14: return run<MfmaCfg<14, mfma_log_tiles(14, false), true>, MfmaCfg<14, mfma_log_tiles(14, true), true>>(op, a);
     default: return WHT_ERR_BAD_DIM;
     }
 }
@@ -190,7 +193,7 @@ static int check_dims(int64_t N, int32_t d, int32_t dtype, Width* w) {
         *w = Width{l, false};
         return WHT_OK;
     }
-    // 12 * 2^m: bfloat16 only, 768 .. 6144
+    // 12 * 2^m: bfloat16 only, 768 .. 12288
     if (d % 12 != 0 || dtype != WHT_DTYPE_BF16 || d < WHT_MIN_D_TWELVE || d > WHT_MAX_D_TWELVE)
         return WHT_ERR_BAD_DIM;
     const int m = log2_exact(d / 12);

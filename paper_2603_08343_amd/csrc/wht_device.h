@@ -137,7 +137,7 @@ struct MfmaCfg {
     static constexpr bool kTwelve = TWELVE;
     static constexpr int n = LOGD, t = LOGT, e = 4 + LOGT, v = 3;
     static constexpr int w = n - 10 - t;        // log2(waves per token)
-    static_assert(n >= 10 && w >= 0 && w <= 1 + t && e <= kMaxRegBits, "bad tile");
+    static_assert(n >= 10 && w >= 0 && w <= 2 * (1 + t) && e <= kMaxRegBits, "bad tile");
     static constexpr PlanDesc plan = make_mfma_plan(n, t);
     static_assert(plan_is_complete(plan), "every stage must run exactly once");
     static constexpr int P = plan.nphase;
@@ -402,12 +402,15 @@ __device__ __forceinline__ void global_put(const float (&r)[C::E], typename C::i
 template <class C, int PH>
 __device__ __forceinline__ void param_get(float (&r)[C::E], const float* p, unsigned thread_elem,
                                           bool ok, float scale) {
+    // Padding lanes of a 12 * 2^m row read block 0 instead (in bounds) and scale it to zero: a load
+    // under a per-lane condition costs the compiler a second copy of every parameter register.
+    const unsigned base = (!C::kTwelve || ok) ? thread_elem : 0u;
+    const float sc = (!C::kTwelve || ok) ? scale : 0.0f;
     static_for<0, C::E / 4>([&](auto i) {
         constexpr int I = decltype(i)::value * 4;
         constexpr unsigned off = C::real(reg_elem_offset(C::plan.ph[PH], C::e, I));
-        float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (!C::kTwelve || ok) q = *reinterpret_cast<const float4*>(p + thread_elem + off);
-        r[I] = q.x * scale; r[I + 1] = q.y * scale; r[I + 2] = q.z * scale; r[I + 3] = q.w * scale;
+        const float4 q = *reinterpret_cast<const float4*>(p + base + off);
+        r[I] = q.x * sc; r[I + 1] = q.y * sc; r[I + 2] = q.z * sc; r[I + 3] = q.w * sc;
     });
 }
 

@@ -147,13 +147,15 @@ constexpr bool plan_is_complete(const PlanDesc& pl) {
 // After round 2 every lane holds 8 consecutive elements per 16 registers -- the layout it loaded
 // in -- so the rounds map the first layout onto itself and leave d/1024 = 2^(t+w) sub-transforms to
 // combine: t "tile" bits in registers (2^t MFMA tiles per wave), w bits across the waves of the
-// token through one LDS exchange into a second layout that holds them in registers.
+// token.  One LDS exchange brings up to 1+t of the wave bits into registers (in place of the first
+// layout's upper register bits, whose stages are done); a token of more than 2^(1+t) waves takes a
+// second exchange for the rest.
 //   first layout : registers (0,1,2, 9, 10..10+t-1), lanes (3..8), waves (10+t..n-1)
-//   second layout: registers (0,1,2, the 1+t-w highest of the first layout's upper register bits,
-//                  n-w..n-1), lanes (3..8), waves (the w replaced bits)
+//   next layouts : registers (0,1,2, the upper register bits of the previous layout that are not
+//                  replaced, the wave bits brought in), lanes (3..8), waves (everything else)
 constexpr PlanDesc make_mfma_plan(int n, int t) {
     PlanDesc pl{};
-    const int e = 4 + t, v = 3, w = n - 10 - t;
+    const int e = 4 + t, v = 3, w = n - 10 - t, c = 1 + t;
     pl.n = n; pl.e = e; pl.v = v; pl.nphase = 0;
     pl.mfma_bits = (1u << 10) - 1u;
     PhaseDesc first{};
@@ -163,20 +165,33 @@ constexpr PlanDesc make_mfma_plan(int n, int t) {
     for (int k = 0; k < t; ++k) first.stages |= 1u << (10 + k);
     fill_thread_bits(first, n, e);
     pl.ph[pl.nphase++] = first;
-    if (w <= 0) return pl;
-    PhaseDesc second{};
-    second.rb[0] = 0; second.rb[1] = 1; second.rb[2] = 2;
-    int q = 3;
-    for (int k = w; k < 1 + t; ++k) second.rb[q++] = first.rb[3 + k];   // kept upper register bits
-    second.stages = 0;
-    for (int k = 0; k < w; ++k) { second.rb[q++] = n - w + k; second.stages |= 1u << (n - w + k); }
-    fill_thread_bits(second, n, e);
-    pl.ph[pl.nphase++] = second;
+    PhaseDesc prev = first;
+    for (int done = 0; done < w;) {
+        const int take = (w - done) < c ? (w - done) : c;
+        PhaseDesc next{};
+        next.rb[0] = 0; next.rb[1] = 1; next.rb[2] = 2;
+        int q = 3;
+        for (int k = take; k < c; ++k) next.rb[q++] = prev.rb[3 + k];     // kept upper register bits
+        next.stages = 0;
+        for (int k = 0; k < take; ++k) {
+            const int bit = n - w + done + k;
+            next.rb[q++] = bit;
+            next.stages |= 1u << bit;
+        }
+        fill_thread_bits(next, n, e);
+        pl.ph[pl.nphase++] = next;
+        prev = next;
+        done += take;
+    }
     return pl;
 }
 
-// tiles per wave (log2) used for a given log2 d
-constexpr int mfma_log_tiles(int logd) { return logd <= 10 ? 0 : (logd <= 13 ? 1 : 2); }
+// tiles per wave (log2) used for a given log2 d.  At d = 2^14 the forward pass takes four tiles per
+// wave (64 values per thread, one exchange), the backward pass two (32 values per thread, two
+// exchanges): its per-thread state (alpha', dalpha, dbeta) does not fit next to 64 values.
+constexpr int mfma_log_tiles(int logd, bool backward) {
+    return logd <= 10 ? 0 : ((logd >= 14 && !backward) ? 2 : 1);
+}
 
 // ---- rows of 12 * 2^m elements on 2^n = 16 * 2^m slots ----------------------------------------
 // Slot index s = (r_hi << 8) | (b << 4) | r_lo  <->  element b * 2^m + (r_hi << 4 | r_lo), m = n - 4:

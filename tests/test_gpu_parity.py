@@ -22,7 +22,7 @@ def _method(d):
     return "matrix" if d <= 512 else "fast"
 
 
-TWELVE_D = [768, 1536, 3072, 6144]      # d = 12 * 2^m: H = P12 (x) Sylvester, bfloat16 only
+TWELVE_D = [768, 1536, 3072, 6144, 12288]      # d = 12 * 2^m: H = P12 (x) Sylvester, bfloat16 only
 
 
 def run_forward(inp):
@@ -118,7 +118,7 @@ def test_twelve_widths_unit_vectors_and_blocks(d):
     assert_io_close(y, ref, "bf16", f"one-hot d={d}")
 
 
-@pytest.mark.parametrize("d,N", [(768, 263), (1536, 67), (6144, 35)])
+@pytest.mark.parametrize("d,N", [(768, 263), (1536, 67), (6144, 35), (12288, 5)])
 def test_forward_residual_twelve_widths(d, N):
     _announce(f"forward+residual d={d} (12 * 2^m) N={N}")
     inp = synth.make_inputs(N, d, "bf16", seed=d + 7)

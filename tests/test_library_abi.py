@@ -46,11 +46,12 @@ P = 0x1000   # a 16-byte-aligned non-null fake address: validation fails before 
     ((P, P, P, 0, 4, 256, 0), NULLP),
     ((P, P, P, P, 4, 768, 0), DIM),        # 12 * 2^m widths: bfloat16 only ...
     ((P, P, P, P, 4, 384, 1), DIM),        # ... from 768 ...
-    ((P, P, P, P, 4, 12288, 1), DIM),      # ... to 6144
+    ((P, P, P, P, 4, 24576, 1), DIM),      # ... to 12288
     ((P, P, P, P, 4, 1000, 1), DIM),       # neither 2^n nor 12 * 2^m
     ((P, P, P, P, 4, 1280, 1), DIM),       # 5 * 2^8
     ((P, P, P, P, 0, 768, 1), OK),         # accepted width, N = 0
     ((P, P, P, P, 0, 6144, 1), OK),
+    ((P, P, P, P, 0, 12288, 1), OK),
     ((P, P, P, P, 4, 16, 0), DIM),         # below WHT_MIN_D
     ((P, P, P, P, 4, 32768, 1), DIM),      # above WHT_MAX_D
     ((P, P, P, P, 4, 16384, 0), DIM),      # above WHT_MAX_D_F32
@@ -110,7 +111,7 @@ def test_workspace_query():
     # rows of 12 * 2^m elements: the partial rows have the row's real length
     assert q(1, 6144, 1) == 2 * 6144 * 4
     assert q(4, 768, 1) == 2 * 768 * 4            # four tokens share a workgroup at d = 768
-    assert q(10, 768, 0) == 0 and q(10, 12288, 1) == 0
+    assert q(10, 768, 0) == 0 and q(10, 24576, 1) == 0
 
 
 def test_missing_library_fails_loudly(monkeypatch):
@@ -151,7 +152,7 @@ int main(void) {
     if (wsq(0, 1024, WHT_DTYPE_BF16) != 0) return 3;
     if (bwd((void *)16, (void *)16, (float *)16, (void *)16, (float *)16, (float *)16, 4, 1024, 7, NULL, 0, NULL)
         != WHT_ERR_BAD_DTYPE) return 4;
-    if (WHT_MIN_D != 32 || WHT_MAX_D != 16384 || WHT_MIN_D_TWELVE != 768 || WHT_MAX_D_TWELVE != 6144) return 5;
+    if (WHT_MIN_D != 32 || WHT_MAX_D != 16384 || WHT_MIN_D_TWELVE != 768 || WHT_MAX_D_TWELVE != 12288) return 5;
     printf("%s|%d\n", wht_affine_status_string(WHT_OK), wht_affine_version());
     return 0;
 }

@@ -22,11 +22,11 @@ def test_schedule_selftest(tmp_path):
     out = subprocess.run([exe], capture_output=True, text=True)
     assert out.returncode == 0, out.stdout
     lines = [l for l in out.stdout.splitlines() if " n=" in l]
-    # butterfly schedule: float32 d = 2^5..2^13, bfloat16 d = 2^5..2^14; matrix-core: d = 2^10..2^14;
-    # rows of 12 * 2^m elements: d = 768..6144
-    assert len(lines) == 9 + 10 + 5 + 4 and all(l.endswith(" ok") for l in lines), out.stdout
-    assert sum(l.startswith("mfma") for l in lines) == 5
-    assert sum(l.startswith("twelve") for l in lines) == 4
+    # butterfly schedule: float32 d = 2^5..2^13, bfloat16 d = 2^5..2^14; matrix-core: d = 2^10..2^14,
+    # with separate forward and backward schedules at 2^14; rows of 12 * 2^m elements: d = 768..12288
+    assert len(lines) == 9 + 10 + 6 + 5 and all(l.endswith(" ok") for l in lines), out.stdout
+    assert sum(l.startswith("mfma") for l in lines) == 6
+    assert sum(l.startswith("twelve") for l in lines) == 5
     # the order-12 factor the kernels carry (their own table) is the oracle's matrix
     out = subprocess.run([exe, "--p12"], capture_output=True, text=True, check=True)
     rows = out.stdout.split()
