@@ -47,18 +47,30 @@ static int grid_for(int64_t N, bool backward) {
     return (int)(groups < cap ? groups : cap);
 }
 
+// Workgroups per cluster of the forward kernel: the configuration's figure when the grid divides
+// into such clusters and every workgroup has several token groups to walk, else the whole grid.
+template <class C>
+static int forward_cluster(int64_t N, int grid) {
+    const int64_t groups = (N + C::G - 1) / C::G;
+    constexpr int want = C::kFwdCluster;
+    if (want > 0 && grid % want == 0 && grid > want && groups >= 4 * (int64_t)grid) return want;
+    return grid;
+}
+
 template <class C>
 static int launch_forward(const void* x, const float* alpha, const float* beta, const void* resid, void* y,
                           int64_t N, hipStream_t stream) {
     using T = typename C::io::elem_t;
+    const int grid = grid_for<C>(N, false);
+    const int cluster = forward_cluster<C>(N, grid);
     if (resid)
-        hipLaunchKernelGGL((forward_kernel<C, true>), dim3(grid_for<C>(N, false)), dim3(C::BT), 0, stream,
+        hipLaunchKernelGGL((forward_kernel<C, true>), dim3(grid), dim3(C::BT), 0, stream,
                            static_cast<const T*>(x), alpha, beta, static_cast<const T*>(resid),
-                           static_cast<T*>(y), N);
+                           static_cast<T*>(y), N, cluster);
     else
-        hipLaunchKernelGGL((forward_kernel<C, false>), dim3(grid_for<C>(N, false)), dim3(C::BT), 0, stream,
+        hipLaunchKernelGGL((forward_kernel<C, false>), dim3(grid), dim3(C::BT), 0, stream,
                            static_cast<const T*>(x), alpha, beta, static_cast<const T*>(nullptr),
-                           static_cast<T*>(y), N);
+                           static_cast<T*>(y), N, cluster);
     return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
 }
 
