@@ -50,9 +50,10 @@ static int grid_for(int64_t N, bool backward) {
 // Workgroups per cluster of the forward kernel: the configuration's figure when the grid divides
 // into such clusters and every workgroup has several token groups to walk, else the whole grid.
 template <class C>
-static int forward_cluster(int64_t N, int grid) {
+static int forward_cluster(int64_t N, int grid, bool resid) {
     const int64_t groups = (N + C::G - 1) / C::G;
-    constexpr int want = C::kFwdCluster;
+    static const int forced = env_int("WHT_AFFINE_FWD_CLUSTER", 0, 65536);   // tuning runs only
+    const int want = forced ? forced : (resid ? C::kFwdClusterResid : C::kFwdCluster);
     if (want > 0 && grid % want == 0 && grid > want && groups >= 4 * (int64_t)grid) return want;
     return grid;
 }
@@ -62,7 +63,7 @@ static int launch_forward(const void* x, const float* alpha, const float* beta, 
                           int64_t N, hipStream_t stream) {
     using T = typename C::io::elem_t;
     const int grid = grid_for<C>(N, false);
-    const int cluster = forward_cluster<C>(N, grid);
+    const int cluster = forward_cluster<C>(N, grid, resid != nullptr);
     if (resid)
         hipLaunchKernelGGL((forward_kernel<C, true>), dim3(grid), dim3(C::BT), 0, stream,
                            static_cast<const T*>(x), alpha, beta, static_cast<const T*>(resid),

@@ -107,7 +107,7 @@ struct Cfg {
     // persistent-grid size in workgroups per CU (measured optima, N = 16384..32768 tokens)
     static constexpr int kFwdGroupsPerCU = v == 2 ? (n >= 13 ? 8 : 4) : (n <= 9 ? 2 : 8);
     static constexpr int kBwdGroupsPerCU = v == 2 ? 1 : 2;
-    static constexpr int kFwdCluster = 0;       // see MfmaCfg
+    static constexpr int kFwdCluster = 0, kFwdClusterResid = 0;     // see MfmaCfg
     static constexpr int kRow = D;              // elements per row in memory
     static constexpr unsigned real(unsigned i) { return i; }
     static constexpr bool valid(unsigned) { return true; }
@@ -163,6 +163,9 @@ struct MfmaCfg {
     // mean over all distances, for +1.5 % in the best case.  Rows of 4 KiB and less show no such
     // dependence and keep the plain interleave.
     static constexpr int kFwdCluster = n >= 12 ? 128 : 0;
+    // with the residual as a third stream two windows measured best (mean 263 us against 274 us
+    // with four and 268 us with one, d = 8192)
+    static constexpr int kFwdClusterResid = n >= 12 ? 256 : 0;
     static constexpr int kRow = TWELVE ? 3 * (D / 4) : D;       // elements per row in memory
     static constexpr unsigned real(unsigned s) {                // slot index -> element index
         return TWELVE ? twelve_elem(s, n) : s;
