@@ -161,6 +161,23 @@ def test_reduction_over_odd_token_counts(N, d, dtype):
     check_backward_full(synth.make_inputs(N, d, dtype, seed=N), f"bwd N={N} d={d}")
 
 
+@pytest.mark.parametrize("N", [2048, 2085, 4099])
+def test_forward_clustered_deal_with_ragged_regions(N):
+    # d = 8192 with at least 4 x 512 token groups: the forward kernels deal the groups to clusters of
+    # workgroups, each with its own contiguous region (four regions, two with the residual); token
+    # counts that do not divide evenly leave the last region short.  Every element is checked.
+    _announce(f"clustered forward d=8192 N={N}")
+    inp = synth.make_inputs(N, 8192, "bf16", seed=N)
+    x, resid = to_gpu(inp.x, "bf16"), to_gpu(inp.dy, "bf16")
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    y = wht.wht_affine_forward(x, a, b)
+    yr = wht.wht_affine_forward_residual(x, a, b, resid)
+    torch.cuda.synchronize()
+    assert_io_close(y, oracle.forward(inp.x, inp.alpha, inp.beta, "fast"), "bf16", f"clustered y N={N}")
+    assert_io_close(yr, oracle.forward_residual(inp.x, inp.alpha, inp.beta, inp.dy, "fast"), "bf16",
+                    f"clustered y+resid N={N}")
+
+
 def test_many_passes_per_workgroup():
     # more token groups than the grid cap: every workgroup loops several times, last pass ragged
     inp = synth.make_inputs(5000, 256, "bf16", seed=3)
