@@ -57,8 +57,10 @@ class Bench:
         self.w = w
         tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
         per_set = (4 if w.backward else 2) * w.N * w.d * io_bytes(w.dtype)
-        # rotate buffer sets so that consecutive steps cannot be served by the 256 MB Infinity Cache
-        self.sets = sets if sets is not None else max(1, min(8, -(-(1 << 30) // per_set)))
+        # rotate buffer sets so that consecutive steps cannot be served by the 256 MB Infinity Cache;
+        # at least three, because the kernels' time also depends (by a few per cent) on the address
+        # distances between the tensors, which differ from set to set
+        self.sets = sets if sets is not None else max(3, min(8, -(-(1 << 30) // per_set)))
         g = torch.Generator(device="cuda").manual_seed(0)
         rng = np.random.Generator(np.random.PCG64(0))
         self.alpha = torch.from_numpy(rng.uniform(0.5, 1.5, w.d).astype(np.float32)).cuda()
