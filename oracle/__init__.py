@@ -9,6 +9,7 @@ arrays into it:
     transform(x, method)                      -> z  = H x                        [N,d] float64
     forward(x, alpha, beta, method)           -> y  = alpha*z + beta             [N,d] float64
     forward_residual(x, alpha, beta, resid)   -> y  = resid + alpha*z + beta     [N,d] float64
+    forward_residual_stats(x, alpha, beta, resid) -> (y, sumsq), sumsq[n] = sum_j y[n,j]^2
     backward(dy, x, alpha, method, ...)       -> dx, dalpha, dbeta               float64
     hadamard_matrix(d)                        -> H_raw (+-1 integers), entry by entry from the
                                                  oracle's sign rule
@@ -38,6 +39,7 @@ def _load():
         lib.wht_oracle_forward.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32]
         lib.wht_oracle_forward_residual.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32]
         lib.wht_oracle_backward.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i32, i32]
+        lib.wht_oracle_row_sumsq.argtypes = [vp, vp, i64, i64]
         lib.wht_oracle_butterfly_stage.argtypes = [vp, i64, i64]
         lib.wht_oracle_butterfly_stage.restype = None
         lib.wht_oracle_sign.argtypes = [ctypes.c_uint32, ctypes.c_uint32]
@@ -167,6 +169,16 @@ def forward_residual(x, alpha, beta, resid, method: str = "fast") -> np.ndarray:
     _check(_load().wht_oracle_forward_residual(_ptr(x), _ptr(alpha), _ptr(beta), _ptr(resid), _ptr(y),
                                                N, d, code, _METHODS[method]))
     return y.reshape(x.shape)
+
+
+def forward_residual_stats(x, alpha, beta, resid, method: str = "fast"):
+    """(y, sumsq): y = resid + alpha*(H x) + beta and sumsq[n] = sum_j y[n,j]^2, the statistic of a
+    following RMS normalisation."""
+    y = forward_residual(x, alpha, beta, resid, method)
+    y2 = np.ascontiguousarray(y.reshape(-1, y.shape[-1]))
+    sumsq = np.empty(y2.shape[0], dtype=np.float64)
+    _check(_load().wht_oracle_row_sumsq(_ptr(y2), _ptr(sumsq), y2.shape[0], y2.shape[1]))
+    return y, sumsq
 
 
 def backward(dy, x, alpha, method: str = "fast", want_dx: bool = True, want_param_grads: bool = True):

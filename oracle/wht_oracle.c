@@ -263,6 +263,23 @@ int wht_oracle_forward_residual(const void *x, const double *alpha, const double
 }
 
 /*
+ * The statistic a following RMS normalisation needs from the residual stream (Sec. 6 names the
+ * interplay with RMSNorm as open; fusing the statistic into the layer's epilogue saves the
+ * normalisation its reduction pass):   sumsq[n] = sum_j y[n][j]^2,   y as returned by
+ * wht_oracle_forward_residual (unrounded).
+ */
+int wht_oracle_row_sumsq(const double *y, double *sumsq, int64_t N, int64_t d)
+{
+    if (!y || !sumsq || N < 0 || d < 1) return -1;
+    for (int64_t n = 0; n < N; ++n) {
+        double acc = 0.0;
+        for (int64_t j = 0; j < d; ++j) acc += y[n * d + j] * y[n * d + j];
+        sumsq[n] = acc;
+    }
+    return 0;
+}
+
+/*
  * Backward.  dy, x: [N,d] of `dtype`; alpha: [d] double.
  * dx: [N,d] double or NULL (skip);  dalpha, dbeta: [d] double or NULL (skip both).
  * The sums over tokens are taken per thread over its contiguous share of tokens, in token order,

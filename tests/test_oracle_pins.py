@@ -206,6 +206,27 @@ def test_forward_residual_special_cases():
 
 # ---------------------------------------------------------------- stored dtypes are widened exactly
 
+def test_forward_residual_stats_special_cases():
+    """sumsq[n] = sum_j y[n,j]^2: with alpha = 1, beta = 0 and no residual it is ||x_n||^2 (H preserves
+    the norm, Sec. 4.1); with x = 0 and no residual it is ||beta||^2; in general numpy's row sums."""
+    N, d = 5, 256
+    x, resid = RNG.standard_normal((N, d)), RNG.standard_normal((N, d))
+    alpha, beta = RNG.uniform(0.5, 1.5, d), RNG.standard_normal(d)
+    zero = np.zeros((N, d))
+    y, s = oracle.forward_residual_stats(x, np.ones(d), np.zeros(d), zero)
+    assert np.allclose(s, np.sum(x * x, axis=1), rtol=1e-12)
+    y, s = oracle.forward_residual_stats(zero, alpha, beta, zero)
+    assert np.allclose(s, np.full(N, np.dot(beta, beta)), rtol=1e-14)
+    y, s = oracle.forward_residual_stats(x, alpha, beta, resid)
+    assert np.array_equal(y, oracle.forward_residual(x, alpha, beta, resid))
+    assert np.allclose(s, np.einsum("nj,nj->n", y, y), rtol=1e-14)
+    # twelve-block width and a hand-worked row: y = (3, -4) -> 25
+    y, s = oracle.forward_residual_stats(np.zeros((1, 2)), np.ones(2), np.array([3.0, -4.0]), np.zeros((1, 2)))
+    assert s.tolist() == [25.0]
+    y, s = oracle.forward_residual_stats(RNG.standard_normal((2, 96)), np.ones(96), np.zeros(96), np.zeros((2, 96)))
+    assert s.shape == (2,) and np.all(s > 0)
+
+
 def test_bf16_and_f32_inputs_widen_exactly():
     import torch
     bits = RNG.integers(0, 1 << 16, size=4096, dtype=np.uint16)
