@@ -374,7 +374,8 @@ def attention_block_context(torch, wht, iters=20):
 
 def fused_residual(torch, wht, synth, name, steps=100, warmup=100):
     """y = resid + alpha (.) Hx + beta in one kernel (3 N d s bytes) against the unfused pair:
-    the layer's forward followed by torch's in-place add on the residual stream (5 N d s bytes)."""
+    the layer's forward followed by torch's in-place add on the residual stream (5 N d s bytes);
+    and the same kernel also delivering sum_j y^2 per token (the following RMS norm's statistic)."""
     w = synth.WORKLOADS[name]
     b = Bench(torch, wht, synth, name)
     tdt = b.x[0].dtype
@@ -389,8 +390,14 @@ def fused_residual(torch, wht, synth, name, steps=100, warmup=100):
         wht.wht_affine_forward(b.x[k], b.alpha, b.beta, y=b.y[k])
         resid[k].add_(b.y[k])
 
+    sumsq = torch.empty(w.N, dtype=torch.float32, device="cuda")
+
+    def fused_stats(i):
+        k = i % b.sets
+        wht.wht_affine_forward_residual_stats(b.x[k], b.alpha, b.beta, resid[k], y=b.y[k], sumsq=sumsq)
+
     out = {"workload": name}
-    for key, fn in (("fused", fused), ("unfused", unfused)):
+    for key, fn in (("fused", fused), ("fused_stats", fused_stats), ("unfused", unfused)):
         for i in range(warmup):
             fn(i)
         a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -101,6 +101,21 @@ int wht_affine_forward_residual(const void *x, const float *alpha, const float *
                                 int64_t N, int32_t d, int32_t dtype, void *stream);
 
 /*
+ * The same, and the statistic of an RMS normalisation that follows the residual stream:
+ *     y = resid + alpha (.) (H x) + beta,      sumsq[n] = sum_j y[n,j]^2.
+ * (Sec. 6 of the paper leaves the interplay of the layer with RMSNorm open; with the statistic
+ * delivered by the layer's epilogue, the normalisation has no reduction pass of its own and can be
+ * folded into its consumer.)  The squares are taken from the float32 values before they are rounded
+ * to `dtype` for the store, and summed in float32 in a fixed order (bit-reproducible).
+ *   sumsq  out  [N]  float32, 4-byte aligned, overwritten.
+ * Its backward is wht_affine_backward as well: the statistic's own gradient belongs to the
+ * normalisation that consumes it.
+ */
+int wht_affine_forward_residual_stats(const void *x, const float *alpha, const float *beta,
+                                      const void *resid, void *y, float *sumsq,
+                                      int64_t N, int32_t d, int32_t dtype, void *stream);
+
+/*
  * Bytes of device scratch wht_affine_backward needs for (N, d, dtype): per-workgroup partial sums
  * of dalpha and dbeta, float32.  Depends on d only through the launch shape; 0 when N = 0 or when
  * the arguments are invalid.  Needs no GPU.

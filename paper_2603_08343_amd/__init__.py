@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     wht_affine_copy_baseline,
     wht_affine_forward,
     wht_affine_forward_residual,
+    wht_affine_forward_residual_stats,
     wht_affine_status_string,
     wht_affine_version,
 )

@@ -18,6 +18,7 @@ _lib = None
 EXPORTS = (
     "wht_affine_forward",
     "wht_affine_forward_residual",
+    "wht_affine_forward_residual_stats",
     "wht_affine_backward_workspace_bytes",
     "wht_affine_backward",
     "wht_affine_copy_baseline",
@@ -50,6 +51,8 @@ def library():
         lib.wht_affine_forward.restype = ctypes.c_int
         lib.wht_affine_forward_residual.argtypes = [vp, vp, vp, vp, vp, i64, i32, i32, vp]
         lib.wht_affine_forward_residual.restype = ctypes.c_int
+        lib.wht_affine_forward_residual_stats.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, vp]
+        lib.wht_affine_forward_residual_stats.restype = ctypes.c_int
         lib.wht_affine_backward_workspace_bytes.argtypes = [i64, i32, i32]
         lib.wht_affine_backward_workspace_bytes.restype = sz
         lib.wht_affine_backward.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, vp, sz, vp]
@@ -72,6 +75,10 @@ def wht_affine_forward_raw(x, alpha, beta, y, N, d, dtype, stream=0) -> int:
 
 def wht_affine_forward_residual_raw(x, alpha, beta, resid, y, N, d, dtype, stream=0) -> int:
     return library().wht_affine_forward_residual(x, alpha, beta, resid, y, N, d, dtype, stream)
+
+
+def wht_affine_forward_residual_stats_raw(x, alpha, beta, resid, y, sumsq, N, d, dtype, stream=0) -> int:
+    return library().wht_affine_forward_residual_stats(x, alpha, beta, resid, y, sumsq, N, d, dtype, stream)
 
 
 def wht_affine_backward_raw(dy, x, alpha, dx, dalpha, dbeta, N, d, dtype, workspace, workspace_bytes,
@@ -167,6 +174,34 @@ def wht_affine_forward_residual(x, alpha, beta, resid, y=None, stream=None):
     if rc != 0:
         raise WhtAffineError(rc, "wht_affine_forward_residual")
     return y
+
+
+def wht_affine_forward_residual_stats(x, alpha, beta, resid, y=None, sumsq=None, stream=None):
+    """(y, sumsq): y = resid + alpha (.) (H x) + beta and sumsq[n] = sum_j y[n,j]^2 (float32 [N]), the
+    statistic of an RMS normalisation that follows the residual stream."""
+    torch = _torch()
+    _check_io(x, "x", torch)
+    _check_io(resid, "resid", torch, like=x)
+    N, d = x.shape
+    _check_param(alpha, "alpha", d, x, torch)
+    _check_param(beta, "beta", d, x, torch)
+    if y is None:
+        y = torch.empty_like(x)
+    else:
+        _check_io(y, "y", torch, like=x)
+    if sumsq is None:
+        sumsq = torch.empty(N, dtype=torch.float32, device=x.device)
+    elif not sumsq.is_cuda or sumsq.dtype != torch.float32 or sumsq.shape != (N,) or not sumsq.is_contiguous() \
+            or sumsq.device != x.device:
+        raise ValueError("sumsq must be a contiguous float32 [N] tensor on x's device")
+    ptrs = (x.data_ptr(), resid.data_ptr(), y.data_ptr(), sumsq.data_ptr()) if N > 0 else (alpha.data_ptr(),) * 4
+    with torch.cuda.device(x.device):
+        rc = wht_affine_forward_residual_stats_raw(ptrs[0], alpha.data_ptr(), beta.data_ptr(), ptrs[1], ptrs[2],
+                                                   ptrs[3], N, d, _dtype_code(x, torch),
+                                                   _stream_handle(stream, torch, x.device))
+    if rc != 0:
+        raise WhtAffineError(rc, "wht_affine_forward_residual_stats")
+    return y, sumsq
 
 
 def wht_affine_backward(dy, x, alpha, dx=None, dalpha=None, dbeta=None, workspace=None, stream=None,

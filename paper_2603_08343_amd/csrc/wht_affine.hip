@@ -60,18 +60,22 @@ static int forward_cluster(int64_t N, int grid, bool resid) {
 
 template <class C>
 static int launch_forward(const void* x, const float* alpha, const float* beta, const void* resid, void* y,
-                          int64_t N, hipStream_t stream) {
+                          float* sumsq, int64_t N, hipStream_t stream) {
     using T = typename C::io::elem_t;
     const int grid = grid_for<C>(N, false);
     const int cluster = forward_cluster<C>(N, grid, resid != nullptr);
-    if (resid)
+    if (resid && sumsq)
+        hipLaunchKernelGGL((forward_kernel<C, true, true>), dim3(grid), dim3(C::BT), 0, stream,
+                           static_cast<const T*>(x), alpha, beta, static_cast<const T*>(resid),
+                           static_cast<T*>(y), sumsq, N, cluster);
+    else if (resid)
         hipLaunchKernelGGL((forward_kernel<C, true>), dim3(grid), dim3(C::BT), 0, stream,
                            static_cast<const T*>(x), alpha, beta, static_cast<const T*>(resid),
-                           static_cast<T*>(y), N, cluster);
+                           static_cast<T*>(y), static_cast<float*>(nullptr), N, cluster);
     else
         hipLaunchKernelGGL((forward_kernel<C, false>), dim3(grid), dim3(C::BT), 0, stream,
                            static_cast<const T*>(x), alpha, beta, static_cast<const T*>(nullptr),
-                           static_cast<T*>(y), N, cluster);
+                           static_cast<T*>(y), static_cast<float*>(nullptr), N, cluster);
     return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
 }
 
@@ -112,7 +116,7 @@ enum class Op { Forward, Backward, Workspace };
 
 struct Args {
     const void* x; const void* dy; const void* resid; const float* alpha; const float* beta;
-    void* y; void* dx; float* dalpha; float* dbeta;
+    void* y; void* dx; float* dalpha; float* dbeta; float* sumsq;
     int64_t N; void* workspace; hipStream_t stream;
     size_t workspace_out;
 };
@@ -121,7 +125,7 @@ struct Args {
 template <class CF, class CB = CF>
 static int run(Op op, Args& a) {
     switch (op) {
-    case Op::Forward:  return launch_forward<CF>(a.x, a.alpha, a.beta, a.resid, a.y, a.N, a.stream);
+    case Op::Forward:  return launch_forward<CF>(a.x, a.alpha, a.beta, a.resid, a.y, a.sumsq, a.N, a.stream);
     case Op::Backward: return launch_backward<CB>(a.dy, a.x, a.alpha, a.dx, a.dalpha, a.dbeta, a.N,
                                                   a.workspace, a.stream);
     default:           a.workspace_out = workspace_for<CB>(a.N); return WHT_OK;
@@ -223,29 +227,39 @@ static int check_dims(int64_t N, int32_t d, int32_t dtype, Width* w) {
 extern "C" {
 
 static int forward_common(const void* x, const float* alpha, const float* beta, const void* resid,
-                          bool with_resid, void* y, int64_t N, int32_t d, int32_t dtype, void* stream) {
+                          bool with_resid, void* y, float* sumsq, bool with_stats, int64_t N, int32_t d,
+                          int32_t dtype, void* stream) {
     using namespace wht;
-    if (!x || !alpha || !beta || !y || (with_resid && !resid)) return WHT_ERR_NULL_PTR;
+    if (!x || !alpha || !beta || !y || (with_resid && !resid) || (with_stats && !sumsq))
+        return WHT_ERR_NULL_PTR;
     Width w{};
     if (int rc = check_dims(N, d, dtype, &w)) return rc;
     if (!aligned16(x) || !aligned16(y) || !aligned16(alpha) || !aligned16(beta) ||
-        (with_resid && !aligned16(resid)))
+        (with_resid && !aligned16(resid)) ||
+        (with_stats && (reinterpret_cast<uintptr_t>(sumsq) & 3u) != 0))
         return WHT_ERR_MISALIGNED;
     if (N == 0) return WHT_OK;
     Args a{};
     a.x = x; a.alpha = alpha; a.beta = beta; a.resid = with_resid ? resid : nullptr; a.y = y; a.N = N;
+    a.sumsq = with_stats ? sumsq : nullptr;
     a.stream = static_cast<hipStream_t>(stream);
     return dispatch(w, dtype, Op::Forward, a);
 }
 
 int wht_affine_forward(const void* x, const float* alpha, const float* beta, void* y, int64_t N,
                        int32_t d, int32_t dtype, void* stream) {
-    return forward_common(x, alpha, beta, nullptr, false, y, N, d, dtype, stream);
+    return forward_common(x, alpha, beta, nullptr, false, y, nullptr, false, N, d, dtype, stream);
 }
 
 int wht_affine_forward_residual(const void* x, const float* alpha, const float* beta, const void* resid,
                                 void* y, int64_t N, int32_t d, int32_t dtype, void* stream) {
-    return forward_common(x, alpha, beta, resid, true, y, N, d, dtype, stream);
+    return forward_common(x, alpha, beta, resid, true, y, nullptr, false, N, d, dtype, stream);
+}
+
+int wht_affine_forward_residual_stats(const void* x, const float* alpha, const float* beta,
+                                      const void* resid, void* y, float* sumsq, int64_t N, int32_t d,
+                                      int32_t dtype, void* stream) {
+    return forward_common(x, alpha, beta, resid, true, y, sumsq, true, N, d, dtype, stream);
 }
 
 size_t wht_affine_backward_workspace_bytes(int64_t N, int32_t d, int32_t dtype) {

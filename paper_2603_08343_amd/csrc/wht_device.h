@@ -640,13 +640,23 @@ struct Walker {
 // but older loads is pending; waiting here, before the new stores, keeps it that way.)
 // RESID fuses the attention block's residual add into the epilogue: resid is one more staged
 // stream, fetched in the layout y is stored in.
-template <class C, bool RESID>
+// STATS (with RESID) also writes sumsq[token] = sum_j y[token][j]^2, taken from the float32 values
+// before they are rounded for the store: the statistic of an RMS normalisation that follows the
+// residual stream.  Each thread squares its values, the lanes of a token add up by butterfly
+// shuffles, and a token that spans several waves adds the wave sums through LDS in a fixed order
+// (one more workgroup barrier per token; the next write to that LDS array is behind the next
+// token's exchange barriers, so nothing else is needed).
+template <class C, bool RESID, bool STATS = false>
 __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::elem_t* x,
                                                         const float* __restrict__ alpha,
                                                         const float* __restrict__ beta,
                                                         const typename C::io::elem_t* resid,
                                                         typename C::io::elem_t* y,
+                                                        float* __restrict__ sumsq,
                                                         int64_t N, int cluster) {
+    static_assert(!STATS || RESID, "the statistic belongs to the residual-stream output");
+    static_assert(!STATS || C::TPT <= 64 || C::P > 1, "a token of several waves has an exchange");
+    __shared__ float wave_sums[STATS ? C::BT / 64 : 1];
     // separate LDS objects: the compiler can then tell that the exchange region's accesses never
     // alias an LDS-direct load in flight, and does not wait for the prefetch before them
     __shared__ __align__(16) float lds[C::kExchangeBytes / 4];
@@ -706,8 +716,30 @@ __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::el
 #pragma unroll
             for (int i = 0; i < C::E; ++i) r[i] = fmaf(r[i], a[i], b[i]);
         }
-        if (more) wait_vmem<0>();
         const int64_t tok = wk.token(grp);
+        if constexpr (STATS) {
+            float sq = 0.0f;
+#pragma unroll
+            for (int i = 0; i < C::E; ++i) sq = fmaf(r[i], r[i], sq);
+            if (C::kTwelve && !tm.last_ok) sq = 0.0f;          // padding lanes hold no elements
+            constexpr int kLanes = C::TPT < 64 ? C::TPT : 64;   // lanes of one wave that share a token
+#pragma unroll
+            for (int off = 1; off < kLanes; off <<= 1) sq += __shfl_xor(sq, off);
+            if constexpr (C::TPT <= 64) {
+                if (t == 0 && tok < N) sumsq[tok] = sq;
+            } else {
+                constexpr int kWaves = C::TPT / 64;             // waves per token
+                if ((threadIdx.x & 63u) == 0) wave_sums[threadIdx.x >> 6] = sq;
+                exchange_barrier();
+                if (t == 0 && tok < N) {
+                    float total = 0.0f;
+#pragma unroll
+                    for (int wv = 0; wv < kWaves; ++wv) total += wave_sums[wk.slot * kWaves + wv];
+                    sumsq[tok] = total;
+                }
+            }
+        }
+        if (more) wait_vmem<0>();
         global_put<C, LAST, !C::kTwelve>(r, y + tok * C::kRow, tm.last_elem, tok < N && tm.last_ok);
     }
 }

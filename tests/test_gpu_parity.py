@@ -210,6 +210,36 @@ def test_forward_residual(d, dtype, N):
                        y.view(torch.int16 if dtype == "bf16" else torch.int32))
 
 
+@pytest.mark.parametrize("d,dtype,N", [(32, "f32", 70), (64, "bf16", 300), (256, "f32", 64), (512, "bf16", 131),
+                                       (1024, "bf16", 263), (2048, "bf16", 67), (4096, "bf16", 35),
+                                       (8192, "bf16", 2085), (16384, "bf16", 5), (8192, "f32", 9),
+                                       (768, "bf16", 263), (1536, "bf16", 67), (6144, "bf16", 35), (12288, "bf16", 5)])
+def test_forward_residual_stats(d, dtype, N):
+    """The fused residual forward that also returns sum_j y^2 per token: y must be bit-identical to
+    the call without the statistic; the statistic is checked against the oracle's (1e-5 relative: it
+    is a float32 sum of d squares of float32 values that themselves carry ~1e-6) and against the sum
+    of squares of the kernel's own stored y (which differs by the rounding of y to its dtype)."""
+    _announce(f"forward+residual+stats d={d} {dtype} N={N}")
+    inp = synth.make_inputs(N, d, dtype, seed=d + 11)
+    x, resid = to_gpu(inp.x, dtype), to_gpu(inp.dy, dtype)
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    y_plain = wht.wht_affine_forward_residual(x, a, b, resid)
+    y, ss = wht.wht_affine_forward_residual_stats(x, a, b, resid)
+    torch.cuda.synchronize()
+    view = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(y.view(view), y_plain.view(view))
+    ref_y, ref_ss = oracle.forward_residual_stats(inp.x, inp.alpha, inp.beta, inp.dy, _method(d))
+    got = ss.cpu().numpy().astype(np.float64)
+    assert got.shape == (N,) and np.all(np.isfinite(got))
+    assert np.max(np.abs(got - ref_ss) / ref_ss) <= 1e-5
+    stored = np.sum(to_f64(y) ** 2, axis=1)
+    assert np.max(np.abs(got - stored) / stored) <= (2e-2 if dtype == "bf16" else 1e-5)
+    # second call with the same inputs: the reduction order is fixed
+    y2, ss2 = wht.wht_affine_forward_residual_stats(x, a, b, resid)
+    torch.cuda.synchronize()
+    assert torch.equal(ss2, ss)
+
+
 def test_forward_residual_full_size_C5():
     w = synth.WORKLOADS["C5_large"]
     _announce("forward+residual at C5 size (sampled tokens)")
@@ -353,6 +383,7 @@ def test_hip_graph_replays_match_eager(d, N):
     x = torch.empty(N, d, device="cuda", dtype=torch.bfloat16)
     dy, resid = torch.empty_like(x), torch.empty_like(x)
     y, yr, dx = torch.empty_like(x), torch.empty_like(x), torch.empty_like(x)
+    yr2, ss = torch.empty_like(x), torch.empty(N, device="cuda")
     da, db = torch.empty(d, device="cuda"), torch.empty(d, device="cuda")
     ws = torch.empty(max(16, wht.wht_affine_backward_workspace_bytes(N, d, wht.DTYPE_BF16)),
                      dtype=torch.uint8, device="cuda")
@@ -360,6 +391,7 @@ def test_hip_graph_replays_match_eager(d, N):
     def step():
         wht.wht_affine_forward(x, a, b, y=y)
         wht.wht_affine_forward_residual(x, a, b, resid, y=yr)
+        wht.wht_affine_forward_residual_stats(x, a, b, resid, y=yr2, sumsq=ss)
         wht.wht_affine_backward(dy, x, a, dx=dx, dalpha=da, dbeta=db, workspace=ws)
 
     def load(seed):
@@ -383,12 +415,13 @@ def test_hip_graph_replays_match_eager(d, N):
         inp = load(seed)
         graph.replay()
         torch.cuda.synchronize()
-        got = [t.clone() for t in (y, yr, dx, da, db)]
-        for t in (y, yr, dx, da, db):
+        got = [t.clone() for t in (y, yr, dx, da, db, yr2, ss)]
+        for t in (y, yr, dx, da, db, yr2, ss):
             t.zero_()
         step()                                        # eager, same buffers
         torch.cuda.synchronize()
-        for name, g, e in zip(("y", "y+resid", "dx", "dalpha", "dbeta"), got, (y, yr, dx, da, db)):
+        for name, g, e in zip(("y", "y+resid", "dx", "dalpha", "dbeta", "y+resid (stats call)", "sumsq"), got,
+                              (y, yr, dx, da, db, yr2, ss)):
             view = torch.int16 if g.dtype == torch.bfloat16 else torch.int32
             assert torch.equal(g.view(view), e.view(view)), f"replay {replay}: {name} differs from eager"
         if replay == 0:

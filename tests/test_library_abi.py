@@ -79,6 +79,16 @@ def test_forward_residual_argument_validation():
     assert call(P, P, P, P, P, 0, 256, 1) == OK
 
 
+def test_forward_residual_stats_argument_validation():
+    call = binding.wht_affine_forward_residual_stats_raw
+    assert call(P, P, P, P, P, 0, 4, 256, 1) == NULLP             # the statistic's output is required
+    assert call(P, P, P, 0, P, P, 4, 256, 1) == NULLP
+    assert call(P, P, P, P, P, P + 2, 4, 256, 1) == ALIGN         # float32: 4-byte aligned
+    assert call(P, P, P, P, P, P + 4, 0, 256, 1) == OK
+    assert call(P, P, P, P, P, P, 4, 100, 1) == DIM
+    assert call(P, P, P, P, P, P, 0, 768, 1) == OK
+
+
 def test_backward_argument_validation():
     ws = binding.wht_affine_backward_workspace_bytes(100, 1024, 1)
     assert ws > 0 and ws % 16 == 0
@@ -143,6 +153,8 @@ def test_header_is_plain_c_and_links(tmp_path):
 int main(void) {
     int (*fwd)(const void *, const float *, const float *, void *, int64_t, int32_t, int32_t, void *) = wht_affine_forward;
     int (*fwdr)(const void *, const float *, const float *, const void *, void *, int64_t, int32_t, int32_t, void *) = wht_affine_forward_residual;
+    int (*fwds)(const void *, const float *, const float *, const void *, void *, float *, int64_t, int32_t, int32_t,
+                void *) = wht_affine_forward_residual_stats;
     size_t (*wsq)(int64_t, int32_t, int32_t) = wht_affine_backward_workspace_bytes;
     int (*bwd)(const void *, const void *, const float *, void *, float *, float *, int64_t, int32_t, int32_t,
                void *, size_t, void *) = wht_affine_backward;
@@ -150,6 +162,8 @@ int main(void) {
     if (fwd(NULL, NULL, NULL, NULL, 4, 256, WHT_DTYPE_F32, NULL) != WHT_ERR_NULL_PTR) return 1;
     if (fwdr((void *)16, (float *)16, (float *)16, (void *)16, (void *)16, 4, 100, WHT_DTYPE_BF16, NULL) != WHT_ERR_BAD_DIM) return 2;
     if (wsq(0, 1024, WHT_DTYPE_BF16) != 0) return 3;
+    if (fwds((void *)16, (float *)16, (float *)16, (void *)16, (void *)16, NULL, 4, 256, WHT_DTYPE_BF16, NULL)
+        != WHT_ERR_NULL_PTR) return 6;
     if (bwd((void *)16, (void *)16, (float *)16, (void *)16, (float *)16, (float *)16, 4, 1024, 7, NULL, 0, NULL)
         != WHT_ERR_BAD_DTYPE) return 4;
     if (WHT_MIN_D != 32 || WHT_MAX_D != 16384 || WHT_MIN_D_TWELVE != 768 || WHT_MAX_D_TWELVE != 12288) return 5;
