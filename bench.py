@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--workload", default="C5_large")
     ap.add_argument("--no-extras", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
-    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
 
@@ -203,11 +203,24 @@ def cpu_baseline(synth, w, target_seconds):
 
     one()                                                 # first call loads the library
     spent, passes = 0.0, 0
-    while spent < target_seconds and passes < 200:
+    while spent < target_seconds and passes < 1000:
         spent += one()
         passes += 1
     secs = spent / passes
-    return {"value": n / secs, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+    cores = oracle.num_threads()
+    # the same sample on one core, for about a fifth of the time
+    single = None
+    try:
+        oracle.set_num_threads(1)
+        spent1, passes1 = 0.0, 0
+        while spent1 < target_seconds / 5 and passes1 < 50:
+            spent1 += one()
+            passes1 += 1
+        single = n / (spent1 / passes1)
+    finally:
+        oracle.set_num_threads(cores)
+    return {"value": n / secs, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "single_core_value": single,
             "sample": f"first {n} of {w.N} tokens of {w.name} (d={w.d}, {w.dtype} inputs, "
                       f"{'forward+backward' if w.backward else 'forward'}), fp64 butterfly oracle, "
                       f"mean of {passes} passes, {spent:.1f} s of CPU time in total"}
