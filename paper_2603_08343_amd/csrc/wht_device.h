@@ -674,7 +674,6 @@ __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::el
     unsigned char* stage = stage_buf + (threadIdx.x >> 6) * (C::NV * 1024);
     unsigned char* stage_r = stage_r_buf + (RESID ? (threadIdx.x >> 6) * (C::NV * 1024) : 0);
 
-    // first token's fetch goes out before anything else; the parameters load in its shadow
     // Token groups are dealt to clusters of `cluster` consecutive workgroups: the token groups are
     // cut into gridDim.x / cluster contiguous regions, and a cluster walks its region interleaved
     // (workgroup j of the cluster takes groups j, j + cluster, ...).  cluster = gridDim.x is the
@@ -684,6 +683,7 @@ __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::el
     const int64_t per = (wk.groups + nclus - 1) / nclus;
     int64_t grp = clus * per + blockIdx.x % cluster;
     const int64_t grp_end = (clus + 1) * per < wk.groups ? (clus + 1) * per : wk.groups;
+    // first token's fetch goes out before anything else; the parameters load in its shadow
     if (grp < grp_end) {
         stage_issue<C, 0>(stage, x + wk.row(grp) * C::kRow, tm.first_elem, tm.first_ok);
         if constexpr (RESID)
