@@ -455,6 +455,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
+    from paper_2603_08343_amd.build import ensure_built
+    ensure_built()                                        # compiles only if nothing is built yet
     wht.library()                                         # fail loudly if the HIP library is missing
     w = synth.WORKLOADS[args.workload]
 

@@ -28,5 +28,13 @@ def build(verbose: bool = False, extra=()) -> str:
     return LIB
 
 
+def ensure_built(verbose: bool = False) -> str:
+    """For harnesses (tests, smoke check, benchmark): compile only if nothing has been built yet.
+    The binding itself never builds: a missing library is an error there."""
+    if not os.path.exists(LIB):
+        build(verbose=verbose)
+    return LIB
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
