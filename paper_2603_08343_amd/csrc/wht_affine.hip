@@ -16,34 +16,13 @@ namespace wht {
 
 constexpr int kNumCU = 256;             // MI355X
 
-// Workgroups launched per CU (the grid is persistent: each workgroup strides over token groups).
-// The per-configuration defaults (C::kFwdGroupsPerCU, C::kBwdGroupsPerCU) are the measured optima;
-// the environment variables exist for tuning runs only.
-static int env_int(const char* name, int fallback, int hi) {
-    const char* v = getenv(name);
-    if (!v || !*v) return fallback;
-    const int x = atoi(v);
-    return (x >= 1 && x <= hi) ? x : fallback;
-}
-static int groups_per_cu_override(bool backward) {      // 0 = not set
-    static const int fwd = env_int("WHT_AFFINE_FWD_GROUPS_PER_CU", 0, 256);
-    static const int bwd = env_int("WHT_AFFINE_BWD_GROUPS_PER_CU", 0, 256);
-    return backward ? bwd : fwd;
-}
-// Absolute grid size, overriding the per-CU figure (0 = not set).
-static int grid_override(bool backward) {
-    static const int fwd = env_int("WHT_AFFINE_FWD_GRID", 0, 65536);
-    static const int bwd = env_int("WHT_AFFINE_BWD_GRID", 0, 65536);
-    return backward ? bwd : fwd;
-}
-
+// Workgroups launched per CU: the grid is persistent, each workgroup strides over token groups.  The
+// per-configuration figures (C::kFwdGroupsPerCU, C::kBwdGroupsPerCU) are measured optima; the launch
+// shape, and with it the backward workspace size, depends on (N, d, dtype) alone.
 template <class C>
 static int grid_for(int64_t N, bool backward) {
     const int64_t groups = (N + C::G - 1) / C::G;
-    const int forced = grid_override(backward);
-    const int per_cu_env = groups_per_cu_override(backward);
-    const int per_cu = per_cu_env ? per_cu_env : (backward ? C::kBwdGroupsPerCU : C::kFwdGroupsPerCU);
-    const int64_t cap = forced ? forced : (int64_t)kNumCU * per_cu;
+    const int64_t cap = (int64_t)kNumCU * (backward ? C::kBwdGroupsPerCU : C::kFwdGroupsPerCU);
     return (int)(groups < cap ? groups : cap);
 }
 
@@ -52,8 +31,7 @@ static int grid_for(int64_t N, bool backward) {
 template <class C>
 static int forward_cluster(int64_t N, int grid, bool resid) {
     const int64_t groups = (N + C::G - 1) / C::G;
-    static const int forced = env_int("WHT_AFFINE_FWD_CLUSTER", 0, 65536);   // tuning runs only
-    const int want = forced ? forced : (resid ? C::kFwdClusterResid : C::kFwdCluster);
+    const int want = resid ? C::kFwdClusterResid : C::kFwdCluster;
     if (want > 0 && grid % want == 0 && grid > want && groups >= 4 * (int64_t)grid) return want;
     return grid;
 }
@@ -86,11 +64,16 @@ static int launch_backward(const void* dy, const void* x, const float* alpha, vo
     const bool grads = dalpha != nullptr;
     const int grid = grid_for<C>(N, grads);      // dx alone streams like a forward pass
 
-    if (grads && dx)
-        hipLaunchKernelGGL((backward_kernel<C, true, true>), dim3(grid), dim3(C::BT), 0, stream,
-                           static_cast<const T*>(dy), static_cast<const T*>(x), alpha, static_cast<T*>(dx),
-                           static_cast<float*>(workspace), N);
-    else if (grads)
+    if (grads && dx) {
+        if constexpr (C::kBwdTeams)
+            hipLaunchKernelGGL((backward_teams_kernel<C>), dim3(grid), dim3(3 * C::BT), 0, stream,
+                               static_cast<const T*>(dy), static_cast<const T*>(x), alpha, static_cast<T*>(dx),
+                               static_cast<float*>(workspace), N);
+        else
+            hipLaunchKernelGGL((backward_kernel<C, true, true>), dim3(grid), dim3(C::BT), 0, stream,
+                               static_cast<const T*>(dy), static_cast<const T*>(x), alpha, static_cast<T*>(dx),
+                               static_cast<float*>(workspace), N);
+    } else if (grads)
         hipLaunchKernelGGL((backward_kernel<C, true, false>), dim3(grid), dim3(C::BT), 0, stream,
                            static_cast<const T*>(dy), static_cast<const T*>(x), alpha, static_cast<T*>(nullptr),
                            static_cast<float*>(workspace), N);
@@ -133,7 +116,9 @@ static int run(Op op, Args& a) {
 }
 
 // Schedule choice: bfloat16 tokens of 1024 elements or more take the matrix-core schedule, the
-// rest the butterfly schedule.  WHT_AFFINE_SCHEDULE=butterfly forces the latter (tuning runs).
+// rest the butterfly schedule.  WHT_AFFINE_SCHEDULE=butterfly in the environment (read once per
+// process; the library's only environment variable) forces the butterfly schedule for those too:
+// it exists so that both schedules of one build can be tested and profiled against each other.
 static bool use_mfma() {
     static const bool on = [] {
         const char* v = getenv("WHT_AFFINE_SCHEDULE");

@@ -108,6 +108,7 @@ struct Cfg {
     static constexpr int kFwdGroupsPerCU = v == 2 ? (n >= 13 ? 8 : 4) : (n <= 9 ? 2 : 8);
     static constexpr int kBwdGroupsPerCU = v == 2 ? 1 : 2;
     static constexpr int kFwdCluster = 0, kFwdClusterResid = 0;     // see MfmaCfg
+    static constexpr bool kBwdTeams = false;    // see MfmaCfg
     static constexpr int kRow = D;              // elements per row in memory
     static constexpr unsigned real(unsigned i) { return i; }
     static constexpr bool valid(unsigned) { return true; }
@@ -154,7 +155,10 @@ struct MfmaCfg {
     // persistent-grid size in workgroups per CU (measured optima at N = 32768 tokens: more
     // workgroups than this only add concurrent streams to the memory system)
     static constexpr int kFwdGroupsPerCU = 2;
-    static constexpr int kBwdGroupsPerCU = TWELVE ? (n == 11 ? 1 : 2) : ((n == 11 || n >= 13) ? 1 : 2);
+    // the full backward of a schedule with one LDS exchange runs on three teams of waves
+    // (backward_teams_kernel), one workgroup per CU
+    static constexpr bool kBwdTeams = plan.nphase == 2 && 3 * BT <= 1024;
+    static constexpr int kBwdGroupsPerCU = kBwdTeams ? 1 : (TWELVE ? (n == 11 ? 1 : 2) : ((n == 11 || n >= 13) ? 1 : 2));
     // Forward: workgroups per cluster (0 = one interleave over the whole grid).  With every
     // workgroup in one moving window of rows, the read stream and the write stream keep a fixed
     // address distance, and for about 40 % of the distances y - x (period 128 MiB, and again 512 KiB)
@@ -874,6 +878,197 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
         }
     }
     }   // GRADS
+}
+
+// One team's per-thread sums (last layout) -> the workgroup's row out[kRow], times `scale`.  With
+// several token slots per workgroup the slots are added through `lds_sum` (an idle region of
+// G * kTokenWords floats), between two workgroup barriers that every wave of the workgroup passes.
+template <class C>
+__device__ __forceinline__ void write_partial_row(const float (&acc)[C::E], float* lds_sum, float* out,
+                                                  float scale, unsigned tid, const ThreadMap<C>& tm) {
+    constexpr int LAST = C::P - 1;
+    if constexpr (C::G == 1) {
+        static_for<0, C::E / 4>([&](auto i) {
+            constexpr int I = decltype(i)::value * 4;
+            constexpr unsigned off = C::real(reg_elem_offset(C::plan.ph[LAST], C::e, I));
+            const float4 q = make_float4(acc[I] * scale, acc[I + 1] * scale, acc[I + 2] * scale, acc[I + 3] * scale);
+            if (!C::kTwelve || tm.last_ok) *reinterpret_cast<float4*>(out + tm.last_elem + off) = q;
+        });
+    } else {
+        lds_put<C, LAST>(acc, lds_sum + tm.lds_off[LAST]);
+        __syncthreads();
+        for (unsigned j = tid; j < (unsigned)C::D; j += C::BT) {
+            float sum = 0.0f;
+#pragma unroll
+            for (int gslot = 0; gslot < C::G; ++gslot) sum += lds_sum[gslot * C::kTokenWords + C::phys(j)];
+            if (C::valid(j)) out[C::real(j)] = sum * scale;
+        }
+        __syncthreads();
+    }
+}
+
+// backward (all three outputs) on three teams of waves per workgroup, 3 * C::BT threads, for the
+// schedules with one LDS exchange per transform.  Wave w of every team holds the same elements of
+// the token, so each SIMD runs one wave of each team and their matrix-core, vector and LDS phases
+// overlap; one workgroup per CU keeps one token group per CU in flight.
+//   X  waves: z = H_raw x (recomputed) and the dalpha sums
+//   Y1 waves: fetch dy, the dbeta sums, alpha' dy, the stages before the exchange
+//   Y2 waves: the stages after the exchange, the matrix-core rounds, store dx -- one token group
+//             behind the other two teams
+// Every wave passes two barriers per token group k, B1(k) and B2(k):
+//   X (k) : [wait x(k); raw <- stage X; issue x(k+1); rounds; register stage; put X]  B1(k)
+//           [get X; last stages; graw <- stage DY[k%2]; sums]                         B2(k)
+//   Y1(k) : [wait dy(k); graw <- stage DY[k%2]; issue dy(k+1) -> DY[(k+1)%2]; sums; alpha'; stages]  B1(k)
+//           [put Y]                                                                   B2(k)
+//   Y2(k) : [get Y of group k-1; register stage; round 1]  B1(k)  [round 2; store dx(k-1)]  B2(k)
+// and Y2 finishes the last group after the last barrier.  What the barriers order:
+//   exchange region X: put before B1(k), get between B1(k) and B2(k), next put after B2(k);
+//   exchange region Y: put between B1(k) and B2(k), get between B2(k) and B1(k+1);
+//   stage DY[k%2]: filled by the Y1 waves' own loads (awaited before B1(k)), read by the X waves
+//   between B1(k) and B2(k), refilled with dy(k+2) after B2(k).
+// All teams run the same number of iterations, so they pass the same number of barriers.
+// dx(k) is stored after x(k) and dy(k) have been read in full, so dx may alias either exactly.
+template <class C>
+__global__ __launch_bounds__(3 * C::BT) void backward_teams_kernel(const typename C::io::elem_t* dy,
+                                                                   const typename C::io::elem_t* x,
+                                                                   const float* __restrict__ alpha,
+                                                                   typename C::io::elem_t* dx,
+                                                                   float* __restrict__ partials,   // [grid][2][kRow]
+                                                                   int64_t N) {
+    static_assert(3 * C::BT <= 1024, "three teams must fit one workgroup");
+    static_assert(C::kMfma && C::P == 2, "one exchange per transform");
+    __shared__ __align__(16) float lds_x[C::kExchangeBytes / 4];
+    __shared__ __align__(16) float lds_g[C::kExchangeBytes / 4];
+    __shared__ __align__(16) unsigned char stage_x_buf[C::kStageBytes];
+    __shared__ __align__(16) unsigned char stage_g_buf[2][C::kStageBytes];
+    constexpr int LAST = 1;
+    const unsigned team = threadIdx.x / C::BT;                // wave-uniform: BT is a multiple of 64
+    const unsigned tid = threadIdx.x % C::BT;
+    const unsigned t = tid % C::TPT;
+    Walker<C> wk{N, (N + C::G - 1) / C::G, tid / C::TPT};
+    ThreadMap<C> tm;
+    tm.init(t, wk.slot);
+    const unsigned wave_off = (tid >> 6) * (C::NV * 1024);
+    unsigned char* stage_x = stage_x_buf + wave_off;
+    unsigned char* stage_g0 = stage_g_buf[0] + wave_off;
+    unsigned char* stage_g1 = stage_g_buf[1] + wave_off;
+
+    const int64_t step = gridDim.x;
+    int64_t grp = blockIdx.x;
+
+    if (team == 0) {
+        HadamardB hb{}, hbp{};
+        hb = make_hadamard_b();
+        if constexpr (C::kTwelve) hbp = make_paley_b(hb);
+        const HadamardB& hb2 = C::kTwelve ? hbp : hb;
+        if (grp < wk.groups) stage_issue<C, 0>(stage_x, x + wk.row(grp) * C::kRow, tm.first_elem, tm.first_ok);
+        float da[C::E];
+#pragma unroll
+        for (int i = 0; i < C::E; ++i) da[i] = 0.0f;
+        for (int par = 0; grp < wk.groups; grp += step, par ^= 1) {
+            const bool more = grp + step < wk.groups;
+            uint4 raw[C::NV], graw[C::NV];
+            wait_vmem<0>();                                     // x(k) has landed
+            stage_read<C>(raw, stage_x);
+            zero_padding<C>(raw, tm.first_ok);
+            if (more) stage_issue<C, 0>(stage_x, x + wk.row(grp + step) * C::kRow, tm.first_elem, tm.first_ok);
+            const int64_t tok = wk.token(grp);
+            const bool active = C::G == 1 || tok < N;
+            float r[C::E], g[C::E];
+            mfma_rounds_from_bf16<C>(r, raw, hb, hb2);
+            run_stages<C, 0>(r);
+            lds_put<C, 0>(r, lds_x + tm.lds_off[0]);
+            exchange_barrier();                                 // B1(k)
+            lds_get<C, LAST>(r, lds_x + tm.lds_off[LAST]);
+            stage_read<C>(graw, par ? stage_g1 : stage_g0);
+            zero_padding<C>(graw, tm.last_ok);
+            run_stages<C, LAST>(r);
+            unpack_all<C>(g, graw);
+            if constexpr (C::G > 1) {
+                if (!active) {
+#pragma unroll
+                    for (int i = 0; i < C::E; ++i) g[i] = 0.0f;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < C::E; ++i) da[i] = fmaf(g[i], r[i], da[i]);
+            exchange_barrier();                                 // B2(k)
+        }
+        write_partial_row<C>(da, lds_x, partials + (size_t)blockIdx.x * 2 * C::kRow, inv_sqrt_d<C>(), tid, tm);
+    } else if (team == 1) {
+        if (grp < wk.groups) stage_issue<C, LAST>(stage_g0, dy + wk.row(grp) * C::kRow, tm.last_elem, tm.last_ok);
+        float a[C::E], db[C::E];
+        param_get<C, LAST>(a, alpha, tm.last_elem, tm.last_ok, inv_sqrt_d<C>());
+#pragma unroll
+        for (int i = 0; i < C::E; ++i) db[i] = 0.0f;
+        for (int par = 0; grp < wk.groups; grp += step, par ^= 1) {
+            const bool more = grp + step < wk.groups;
+            uint4 graw[C::NV];
+            wait_vmem<0>();                                     // dy(k) has landed
+            stage_read<C>(graw, par ? stage_g1 : stage_g0);
+            zero_padding<C>(graw, tm.last_ok);
+            if (more) stage_issue<C, LAST>(par ? stage_g0 : stage_g1, dy + wk.row(grp + step) * C::kRow, tm.last_elem, tm.last_ok);
+            float g[C::E];
+            unpack_all<C>(g, graw);
+            if (C::G == 1 || wk.token(grp) < N) {               // a ragged last group's clamped rows add nothing
+#pragma unroll
+                for (int i = 0; i < C::E; ++i) db[i] += g[i];
+            }
+#pragma unroll
+            for (int i = 0; i < C::E; ++i) g[i] *= a[i];
+            run_stages<C, LAST>(g);
+            exchange_barrier();                                 // B1(k): the Y2 waves have read token k-1
+            lds_put<C, LAST>(g, lds_g + tm.lds_off[LAST]);
+            exchange_barrier();                                 // B2(k)
+        }
+        // the stage buffers are idle now (same size as an exchange region)
+        write_partial_row<C>(db, reinterpret_cast<float*>(&stage_g_buf[0][0]),
+                             partials + (size_t)blockIdx.x * 2 * C::kRow + C::kRow, 1.0f, tid, tm);
+    } else {
+        HadamardB hb{}, hbp{};
+        hb = make_hadamard_b();
+        if constexpr (C::kTwelve) hbp = make_paley_b(hb);
+        const HadamardB& hb2 = C::kTwelve ? hbp : hb;
+        int64_t prev = -1;                                      // token group whose Y data is in the exchange region
+        auto first_half = [&](float (&g)[C::E], f32x16 (&d1)[C::T]) {
+            lds_get<C, 0>(g, lds_g + tm.lds_off[0]);
+            run_stages<C, 0>(g);
+            static_for<0, C::T>([&](auto tile) {
+                constexpr int Tl = decltype(tile)::value;
+                d1[Tl] = hadamard_round_f32(&g[16 * Tl], hb);
+            });
+        };
+        auto second_half = [&](float (&g)[C::E], f32x16 (&d1)[C::T], int64_t grp_done) {
+            static_for<0, C::T>([&](auto tile) {
+                constexpr int Tl = decltype(tile)::value;
+                float v[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) v[i] = d1[Tl][i];
+                const f32x16 d2 = hadamard_round_f32(v, hb2);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) g[16 * Tl + i] = d2[i];
+            });
+            const int64_t tok = wk.token(grp_done);
+            const bool active = C::G == 1 || tok < N;
+            global_put<C, 0>(g, dx + tok * C::kRow, tm.first_elem, active && tm.first_ok);
+        };
+        for (; grp < wk.groups; grp += step) {
+            float g[C::E];
+            f32x16 d1[C::T];
+            if (prev >= 0) first_half(g, d1);
+            exchange_barrier();                                 // B1(k)
+            if (prev >= 0) second_half(g, d1, prev);
+            exchange_barrier();                                 // B2(k): token k is in the exchange region
+            prev = grp;
+        }
+        if (prev >= 0) {
+            float g[C::E];
+            f32x16 d1[C::T];
+            first_half(g, d1);
+            second_half(g, d1, prev);
+        }
+        if constexpr (C::G > 1) { __syncthreads(); __syncthreads(); }   // the other teams' closing barriers
+    }
 }
 
 // out[which][j] = sum over rows of partials[row][which][j].  Workgroup = CG float4 columns x

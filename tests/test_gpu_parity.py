@@ -1,7 +1,7 @@
 """GPU parity: the HIP kernels, called through the C ABI, against the CPU oracle on identical
-seeded inputs.  Element by element at sizes the oracle finishes in seconds (several workgroup
-passes and a ragged tail), and at the benchmark's full sizes on sampled tokens (y, dx: every token
-is independent, so a sample is checked exactly) plus the full dalpha/dbeta reductions."""
+seeded inputs, element by element: at sizes the oracle finishes in seconds (several workgroup
+passes and a ragged tail) and at the benchmark's full sizes, where every token of y and dx is
+compared (the oracle walks the tensor in chunks) next to the full dalpha/dbeta reductions."""
 import numpy as np
 import pytest
 import torch
@@ -9,7 +9,7 @@ import torch
 import oracle
 import paper_2603_08343_amd as wht
 from paper_2603_08343_amd import binding, synth
-from parity import assert_grad_close, assert_io_close, to_f64, to_gpu
+from parity import assert_grad_close, assert_io_close, nan_filled, to_f64, to_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -53,6 +53,16 @@ def check_backward_full(inp, what):
     assert_io_close(dx, rdx.reshape(inp.N, inp.d), inp.dtype, f"{what} dx")
     assert_grad_close(da, rda, f"{what} dalpha")
     assert_grad_close(db, rdb, f"{what} dbeta")
+
+
+CHUNK = 4096      # tokens per oracle call at full size (bounds the float64 working set)
+
+
+def _assert_all_tokens(got_t, ref_of_chunk, N, dtype, what):
+    """Every token of a full-size output against the oracle, CHUNK tokens at a time."""
+    for lo in range(0, N, CHUNK):
+        hi = min(N, lo + CHUNK)
+        assert_io_close(got_t[lo:hi], ref_of_chunk(lo, hi), dtype, f"{what} tokens {lo}..{hi - 1}")
 
 
 ALL_D = [32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384]
@@ -136,20 +146,25 @@ def test_twelve_widths_reduction_over_odd_token_counts(N):
     check_backward_full(synth.make_inputs(N, 768, "bf16", seed=N), f"bwd N={N} d=768")
 
 
-def test_twelve_width_full_size_sampled():
-    # the paper's Base width at a training-sized batch: sampled tokens for y and dx, full reductions
-    N, d = 32768, 1536
-    _announce(f"full size N={N} d={d} (sampled tokens)")
+@pytest.mark.parametrize("d", [1536, 6144])
+def test_twelve_width_full_size(d):
+    # the paper's Base width, and the widest 12 * 2^m row of the benchmark, at a training-sized
+    # batch: every token of y and dx, full reductions
+    N = 32768
+    _announce(f"full size N={N} d={d}: generating inputs")
     inp = synth.make_inputs(N, d, "bf16", seed=0)
-    idx = _sample_tokens(N, 64, seed=6)
-    y = run_forward(inp)
-    assert_io_close(y[torch.from_numpy(idx).cuda()], oracle.forward(inp.x[idx], inp.alpha, inp.beta, "fast"),
-                    "bf16", "d=1536 y (sampled tokens)")
-    dx, da, db = run_backward(inp)
-    rdx, rda, rdb = oracle.backward(inp.dy, inp.x, inp.alpha, "fast")
-    assert_io_close(dx[torch.from_numpy(idx).cuda()], rdx[idx], "bf16", "d=1536 dx (sampled tokens)")
-    assert_grad_close(da, rda, "d=1536 dalpha")
-    assert_grad_close(db, rdb, "d=1536 dbeta")
+    x, dy = to_gpu(inp.x, "bf16"), to_gpu(inp.dy, "bf16")
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    y = wht.wht_affine_forward(x, a, b, y=nan_filled(N, d, "bf16"))
+    dx, da, db = wht.wht_affine_backward(dy, x, a, dx=nan_filled(N, d, "bf16"))
+    torch.cuda.synchronize()
+    _announce(f"d={d}: every token against the oracle")
+    _assert_all_tokens(y, lambda lo, hi: oracle.forward(inp.x[lo:hi], inp.alpha, inp.beta, "fast"), N, "bf16", f"d={d} y")
+    _assert_all_tokens(dx, lambda lo, hi: oracle.backward(inp.dy[lo:hi], inp.x[lo:hi], inp.alpha, "fast",
+                                                          want_param_grads=False)[0], N, "bf16", f"d={d} dx")
+    _, rda, rdb = oracle.backward(inp.dy, inp.x, inp.alpha, "fast", want_dx=False)
+    assert_grad_close(da, rda, f"d={d} dalpha")
+    assert_grad_close(db, rdb, f"d={d} dbeta")
 
 
 @pytest.mark.parametrize("N", [1, 2, 3, 127, 128, 129, 1031])
@@ -242,16 +257,14 @@ def test_forward_residual_stats(d, dtype, N):
 
 def test_forward_residual_full_size_C5():
     w = synth.WORKLOADS["C5_large"]
-    _announce("forward+residual at C5 size (sampled tokens)")
+    _announce("forward+residual at C5 size, every token")
     inp = synth.make_workload("C5_large")
-    idx = _sample_tokens(w.N, 32, seed=5)
     x, resid = to_gpu(inp.x, "bf16"), to_gpu(inp.dy, "bf16")
     a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
-    y = wht.wht_affine_forward_residual(x, a, b, resid)
+    y = wht.wht_affine_forward_residual(x, a, b, resid, y=nan_filled(w.N, w.d, "bf16"))
     torch.cuda.synchronize()
-    ref = oracle.forward_residual(inp.x[idx], inp.alpha, inp.beta, inp.dy[idx], "fast")
-    assert_io_close(y[torch.from_numpy(idx).cuda()], ref, "bf16", "C5 fwd+resid (sampled tokens)")
-    assert torch.all(torch.isfinite(y.float()))
+    _assert_all_tokens(y, lambda lo, hi: oracle.forward_residual(inp.x[lo:hi], inp.alpha, inp.beta, inp.dy[lo:hi], "fast"),
+                       w.N, "bf16", "C5 fwd+resid")
 
 
 # ------------------------------------------------------------------ the benchmark configurations
@@ -272,46 +285,36 @@ def test_config_C4_decode(N):
     check_forward_full(inp, f"C4 N={N}")
 
 
-def _sample_tokens(N, count, seed):
-    rng = np.random.default_rng(seed)
-    idx = np.unique(np.concatenate([[0, 1, N // 2, N - 2, N - 1], rng.integers(0, N, size=count)]))
-    return idx
-
-
 def _full_size(name, check_bwd):
     w = synth.WORKLOADS[name]
     _announce(f"{name} full size N={w.N} d={w.d} {w.dtype}: generating inputs")
     inp = synth.make_workload(name)
-    idx = _sample_tokens(w.N, 48, seed=w.d)
-    _announce(f"{name}: forward on GPU")
-    y = run_forward(inp)
-    ref_y = oracle.forward(inp.x[idx], inp.alpha, inp.beta, "fast")
-    assert_io_close(y[torch.from_numpy(idx).cuda()], ref_y, inp.dtype, f"{name} y (sampled tokens)")
+    x = to_gpu(inp.x, inp.dtype)
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    _announce(f"{name}: forward on GPU, then every token against the oracle")
+    y = wht.wht_affine_forward(x, a, b, y=nan_filled(w.N, w.d, inp.dtype))
+    torch.cuda.synchronize()
+    _assert_all_tokens(y, lambda lo, hi: oracle.forward(inp.x[lo:hi], inp.alpha, inp.beta, "fast"),
+                       w.N, inp.dtype, f"{name} y")
     # a few tokens against the O(d^2) definition as well
-    few = idx[:6]
+    few = np.array([0, 1, w.N // 2, w.N - 2, w.N - 1])
     assert_io_close(y[torch.from_numpy(few).cuda()], oracle.forward(inp.x[few], inp.alpha, inp.beta, "matrix"),
                     inp.dtype, f"{name} y (definition)")
-    # every output finite and written (no token skipped): the oracle-independent property that
-    # sum_j (y - beta)^2 / alpha^2 = ||x||^2 per token is checked loosely on all tokens
-    yf = y.float()
-    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
-    z2 = (((yf - b) / a) ** 2).sum(dim=1)
-    xt = to_gpu(inp.x, inp.dtype).float()
-    x2 = (xt ** 2).sum(dim=1)
-    assert torch.all(torch.isfinite(yf))
-    assert float(((z2 - x2).abs() / x2).max()) < 2e-2, f"{name}: norm preservation violated on some token"
-    del y, yf, xt, z2, x2
+    del y
     if not check_bwd:
         return
     _announce(f"{name}: backward on GPU")
-    dx, da, db = run_backward(inp)
+    dy = to_gpu(inp.dy, inp.dtype)
+    dx, da, db = wht.wht_affine_backward(dy, x, a, dx=nan_filled(w.N, w.d, inp.dtype))
+    torch.cuda.synchronize()
     _announce(f"{name}: oracle dalpha/dbeta over all {w.N} tokens")
     _, rda, rdb = oracle.backward(inp.dy, inp.x, inp.alpha, "fast", want_dx=False)
     assert_grad_close(da, rda, f"{name} dalpha")
     assert_grad_close(db, rdb, f"{name} dbeta")
-    rdx, _, _ = oracle.backward(inp.dy[idx], inp.x[idx], inp.alpha, "fast", want_param_grads=False)
-    assert_io_close(dx[torch.from_numpy(idx).cuda()], rdx, inp.dtype, f"{name} dx (sampled tokens)")
-    assert torch.all(torch.isfinite(dx.float()))
+    _announce(f"{name}: dx, every token against the oracle")
+    _assert_all_tokens(dx, lambda lo, hi: oracle.backward(inp.dy[lo:hi], inp.x[lo:hi], inp.alpha, "fast",
+                                                          want_param_grads=False)[0],
+                       w.N, inp.dtype, f"{name} dx")
 
 
 def test_config_C2_training_full_size():
@@ -369,6 +372,44 @@ def test_in_place_and_preallocated_outputs():
     assert torch.equal(x2.view(torch.int16), y_ref.view(torch.int16))
     assert torch.equal(dx2.view(torch.int16), dx_ref.view(torch.int16))
     assert torch.equal(da2, da_ref) and torch.equal(db2, db_ref)
+
+
+@pytest.mark.parametrize("d,dtype,N", [(4096, "bf16", 523), (8192, "bf16", 261), (6144, "bf16", 70), (2048, "bf16", 300),
+                                       (1024, "f32", 67)])
+@pytest.mark.parametrize("alias", ["x", "dy"])
+def test_backward_dx_aliases_an_input(d, dtype, N, alias):
+    # the header allows dx to alias x or dy exactly: several token groups per workgroup, so that
+    # stores of one group and prefetches of the next are in flight together
+    _announce(f"backward in place dx={alias} d={d} {dtype} N={N}")
+    inp = synth.make_inputs(N, d, dtype, seed=d + N)
+    x, dy = to_gpu(inp.x, dtype), to_gpu(inp.dy, dtype)
+    a = torch.from_numpy(inp.alpha).cuda()
+    target = x if alias == "x" else dy
+    dx, da, db = wht.wht_affine_backward(dy, x, a, dx=target)
+    torch.cuda.synchronize()
+    assert dx.data_ptr() == target.data_ptr()
+    rdx, rda, rdb = oracle.backward(inp.dy, inp.x, inp.alpha, _method(d))
+    assert_io_close(dx, rdx, dtype, f"in place dx={alias} d={d}")
+    assert_grad_close(da, rda, f"in place dx={alias} d={d} dalpha")
+    assert_grad_close(db, rdb, f"in place dx={alias} d={d} dbeta")
+
+
+@pytest.mark.parametrize("N", [4099])
+def test_float32_many_tokens_at_the_widest_row(N):
+    # float32 I/O at d = 8192 with more token groups than workgroups and a ragged tail
+    _announce(f"float32 d=8192 N={N}")
+    inp = synth.make_inputs(N, 8192, "f32", seed=3)
+    check_forward_full(inp, "f32 d=8192 fwd")
+    check_backward_full(inp, "f32 d=8192 bwd")
+
+
+@pytest.mark.parametrize("d,N", [(4096, 1), (4096, 2), (4096, 3), (4096, 511), (4096, 513), (4096, 1031), (8192, 255),
+                                 (8192, 256), (8192, 257), (8192, 600), (3072, 515), (6144, 259)])
+def test_backward_teams_kernel_token_counts(d, N):
+    # the three-team backward kernel (one LDS exchange per transform: d = 4096, 8192, 3072, 6144): fewer
+    # token groups than workgroups, exactly as many, one more, ragged last groups
+    _announce(f"backward (teams) d={d} N={N}")
+    check_backward_full(synth.make_inputs(N, d, "bf16", seed=7 * d + N), f"teams bwd d={d} N={N}")
 
 
 @pytest.mark.parametrize("d,N", [(4096, 16), (8192, 70), (1536, 33), (256, 40)])
