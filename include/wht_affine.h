@@ -147,6 +147,27 @@ int wht_affine_backward(const void *dy, const void *x, const float *alpha,
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * wht_affine_backward for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and results (bit for
+ * bit) as wht_affine_backward, without the workspace: the per-workgroup partial sums go to a buffer
+ * of WHT_STATIC_WORKSPACE_BYTES that is part of the library's code object (every GPU the library
+ * runs on holds one until the process ends).  The call allocates and frees nothing.
+ *   - A call that would need more than WHT_STATIC_WORKSPACE_BYTES of partial sums
+ *     (wht_affine_backward_workspace_bytes(N, d, dtype); today: d > 8192) returns WHT_ERR_WORKSPACE
+ *     and enqueues nothing.
+ *   - All calls on one GPU share that GPU's buffer.  Calls on one stream are ordered and safe; two
+ *     calls that may run at the same time on one GPU (different streams) race on it -- give those
+ *     their own workspaces through wht_affine_backward.  The buffer's contents between calls are
+ *     unspecified; nothing in it has to start at zero.
+ *   - The first call on a GPU looks the buffer's address up once (with that GPU current); if that
+ *     fails the call returns WHT_ERR_LAUNCH.
+ */
+#define WHT_STATIC_WORKSPACE_BYTES (16u << 20)
+int wht_affine_backward_static(const void *dy, const void *x, const float *alpha,
+                               void *dx, float *dalpha, float *dbeta,
+                               int64_t N, int32_t d, int32_t dtype, void *stream);
+
+/*
  * Measurement aid, not part of the layer: dst[i] = src[i] for `bytes` bytes (a multiple of 16) with
  * the same 16-byte-per-lane access pattern the layer's kernels use.  It gives the benchmark the
  * bandwidth a plain streaming kernel reaches on this GPU and a known-size reference for the

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     library,
     library_path,
     wht_affine_backward,
+    wht_affine_backward_static,
     wht_affine_backward_workspace_bytes,
     wht_affine_copy_baseline,
     wht_affine_forward,

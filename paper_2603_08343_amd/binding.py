@@ -21,6 +21,7 @@ EXPORTS = (
     "wht_affine_forward_residual_stats",
     "wht_affine_backward_workspace_bytes",
     "wht_affine_backward",
+    "wht_affine_backward_static",
     "wht_affine_copy_baseline",
     "wht_affine_status_string",
     "wht_affine_version",
@@ -57,6 +58,8 @@ def library():
         lib.wht_affine_backward_workspace_bytes.restype = sz
         lib.wht_affine_backward.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, vp, sz, vp]
         lib.wht_affine_backward.restype = ctypes.c_int
+        lib.wht_affine_backward_static.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, vp]
+        lib.wht_affine_backward_static.restype = ctypes.c_int
         lib.wht_affine_copy_baseline.argtypes = [vp, vp, sz, vp]
         lib.wht_affine_copy_baseline.restype = ctypes.c_int
         lib.wht_affine_status_string.argtypes = [ctypes.c_int]
@@ -85,6 +88,13 @@ def wht_affine_backward_raw(dy, x, alpha, dx, dalpha, dbeta, N, d, dtype, worksp
                             stream=0) -> int:
     return library().wht_affine_backward(dy, x, alpha, dx, dalpha, dbeta, N, d, dtype, workspace,
                                          workspace_bytes, stream)
+
+
+def wht_affine_backward_static_raw(dy, x, alpha, dx, dalpha, dbeta, N, d, dtype, stream=0) -> int:
+    return library().wht_affine_backward_static(dy, x, alpha, dx, dalpha, dbeta, N, d, dtype, stream)
+
+
+STATIC_WORKSPACE_BYTES = 16 << 20       # WHT_STATIC_WORKSPACE_BYTES
 
 
 def wht_affine_backward_workspace_bytes(N, d, dtype) -> int:
@@ -213,7 +223,9 @@ def wht_affine_backward(dy, x, alpha, dx=None, dalpha=None, dbeta=None, workspac
     if not want_dx and not want_param_grads:
         raise ValueError("nothing to compute: want_dx and want_param_grads are both False")
     _check_io(dy, "dy", torch)
-    if want_param_grads or x is not None:
+    if want_param_grads and x is None:
+        raise ValueError("x is needed for the parameter gradients (want_param_grads=True)")
+    if x is not None:
         _check_io(x, "x", torch, like=dy)
     N, d = dy.shape
     _check_param(alpha, "alpha", d, dy, torch)
@@ -256,6 +268,40 @@ def wht_affine_backward(dy, x, alpha, dx=None, dalpha=None, dbeta=None, workspac
     if rc != 0:
         raise WhtAffineError(rc, "wht_affine_backward")
     return dx, dalpha, dbeta
+
+def wht_affine_backward_static(dy, x, alpha, dx=None, dalpha=None, dbeta=None, stream=None):
+    """wht_affine_backward without a workspace: the library's own static scratch holds the partial
+    sums (for callers that must not allocate; pass dx, dalpha and dbeta in and nothing is
+    allocated here either).  Returns (dx, dalpha, dbeta)."""
+    torch = _torch()
+    _check_io(dy, "dy", torch)
+    if x is None:
+        raise ValueError("x is needed for the parameter gradients")
+    _check_io(x, "x", torch, like=dy)
+    N, d = dy.shape
+    _check_param(alpha, "alpha", d, dy, torch)
+    if dx is None:
+        dx = torch.empty_like(dy)
+    else:
+        _check_io(dx, "dx", torch, like=dy)
+    if dalpha is None:
+        dalpha = torch.empty(d, dtype=torch.float32, device=dy.device)
+    else:
+        _check_param(dalpha, "dalpha", d, dy, torch)
+    if dbeta is None:
+        dbeta = torch.empty(d, dtype=torch.float32, device=dy.device)
+    else:
+        _check_param(dbeta, "dbeta", d, dy, torch)
+    dummy = alpha.data_ptr()
+    ptrs = (dy.data_ptr(), x.data_ptr(), dx.data_ptr()) if N > 0 else (dummy,) * 3
+    with torch.cuda.device(dy.device):
+        rc = wht_affine_backward_static_raw(ptrs[0], ptrs[1], alpha.data_ptr(), ptrs[2], dalpha.data_ptr(),
+                                            dbeta.data_ptr(), N, d, _dtype_code(dy, torch),
+                                            _stream_handle(stream, torch, dy.device))
+    if rc != 0:
+        raise WhtAffineError(rc, "wht_affine_backward_static")
+    return dx, dalpha, dbeta
+
 
 def wht_affine_copy_baseline(src, dst, stream=None):
     """dst <- src with the kernels' access pattern (measurement aid)."""

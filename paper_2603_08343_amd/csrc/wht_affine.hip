@@ -6,6 +6,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/wht_affine.h"
 #include "wht_device.h"
 
@@ -185,6 +187,33 @@ static int log2_exact(int32_t d) {
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// ------------------------------------------------------------------------------------------------
+// Partial-sum scratch that lives in the library's own code object, for wht_affine_backward_static:
+// callers that cannot allocate pass no workspace.  Every GPU the library runs on holds its own copy
+// of the array, at its own address, until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress: what kernels and copies take is the device address it returns.
+static __device__ __align__(256) unsigned char scratch[WHT_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static void* scratch_address[kMaxDevices];       // per device, filled on the first call there
+
+// Device address of the current device's copy of `scratch`, or nullptr if it cannot be had.
+static void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_address[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        scratch_address[dev] = ptr;
+    }
+    return scratch_address[dev];
+}
+
 static int check_dims(int64_t N, int32_t d, int32_t dtype, Width* w) {
     if (dtype != WHT_DTYPE_F32 && dtype != WHT_DTYPE_BF16) return WHT_ERR_BAD_DTYPE;
     if (N < 0) return WHT_ERR_BAD_DIM;
@@ -257,9 +286,11 @@ size_t wht_affine_backward_workspace_bytes(int64_t N, int32_t d, int32_t dtype) 
     return a.workspace_out;
 }
 
-int wht_affine_backward(const void* dy, const void* x, const float* alpha, void* dx, float* dalpha,
-                        float* dbeta, int64_t N, int32_t d, int32_t dtype, void* workspace,
-                        size_t workspace_bytes, void* stream) {
+// Both backward entry points: `own_scratch` takes the partial-sum workspace from the library's
+// static buffer instead of the caller.
+static int backward_common(const void* dy, const void* x, const float* alpha, void* dx, float* dalpha,
+                           float* dbeta, int64_t N, int32_t d, int32_t dtype, void* workspace,
+                           size_t workspace_bytes, bool own_scratch, void* stream) {
     using namespace wht;
     const bool grads = dalpha != nullptr || dbeta != nullptr;
     if (!dy || !alpha) return WHT_ERR_NULL_PTR;
@@ -278,13 +309,30 @@ int wht_affine_backward(const void* dy, const void* x, const float* alpha, void*
     }
     if (grads) {
         const size_t need = wht_affine_backward_workspace_bytes(N, d, dtype);
-        if (!workspace || workspace_bytes < need) return WHT_ERR_WORKSPACE;
-        if (!aligned16(workspace)) return WHT_ERR_MISALIGNED;
+        if (own_scratch) {
+            if (need > (size_t)WHT_STATIC_WORKSPACE_BYTES) return WHT_ERR_WORKSPACE;
+            workspace = static_scratch();
+            if (!workspace) return WHT_ERR_LAUNCH;
+        } else {
+            if (!workspace || workspace_bytes < need) return WHT_ERR_WORKSPACE;
+            if (!aligned16(workspace)) return WHT_ERR_MISALIGNED;
+        }
     }
     Args a{};
     a.dy = dy; a.x = x; a.alpha = alpha; a.dx = dx; a.dalpha = dalpha; a.dbeta = dbeta; a.N = N;
     a.workspace = workspace; a.stream = s;
     return dispatch(w, dtype, Op::Backward, a);
+}
+
+int wht_affine_backward(const void* dy, const void* x, const float* alpha, void* dx, float* dalpha,
+                        float* dbeta, int64_t N, int32_t d, int32_t dtype, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+    return backward_common(dy, x, alpha, dx, dalpha, dbeta, N, d, dtype, workspace, workspace_bytes, false, stream);
+}
+
+int wht_affine_backward_static(const void* dy, const void* x, const float* alpha, void* dx, float* dalpha,
+                               float* dbeta, int64_t N, int32_t d, int32_t dtype, void* stream) {
+    return backward_common(dy, x, alpha, dx, dalpha, dbeta, N, d, dtype, nullptr, 0, true, stream);
 }
 
 int wht_affine_copy_baseline(const void* src, void* dst, size_t bytes, void* stream) {
@@ -308,7 +356,7 @@ const char* wht_affine_status_string(int status) {
     case WHT_ERR_BAD_DIM:    return "d must be a power of two in [WHT_MIN_D, WHT_MAX_D] (WHT_MAX_D_F32 for float32) or, for bfloat16, 12*2^m in [WHT_MIN_D_TWELVE, WHT_MAX_D_TWELVE]; N >= 0";
     case WHT_ERR_BAD_DTYPE:  return "dtype must be WHT_DTYPE_F32 or WHT_DTYPE_BF16";
     case WHT_ERR_MISALIGNED: return "tensor pointers must be 16-byte aligned";
-    case WHT_ERR_WORKSPACE:  return "workspace is NULL or smaller than wht_affine_backward_workspace_bytes";
+    case WHT_ERR_WORKSPACE:  return "workspace is NULL or smaller than wht_affine_backward_workspace_bytes (wht_affine_backward_static: the call needs more than WHT_STATIC_WORKSPACE_BYTES)";
     case WHT_ERR_LAUNCH:     return "the HIP runtime refused a kernel launch";
     default:                 return "unknown status";
     }

@@ -158,6 +158,8 @@ int main(void) {
     size_t (*wsq)(int64_t, int32_t, int32_t) = wht_affine_backward_workspace_bytes;
     int (*bwd)(const void *, const void *, const float *, void *, float *, float *, int64_t, int32_t, int32_t,
                void *, size_t, void *) = wht_affine_backward;
+    int (*bwds)(const void *, const void *, const float *, void *, float *, float *, int64_t, int32_t, int32_t,
+                void *) = wht_affine_backward_static;
     /* argument validation happens before anything touches the GPU */
     if (fwd(NULL, NULL, NULL, NULL, 4, 256, WHT_DTYPE_F32, NULL) != WHT_ERR_NULL_PTR) return 1;
     if (fwdr((void *)16, (float *)16, (float *)16, (void *)16, (void *)16, 4, 100, WHT_DTYPE_BF16, NULL) != WHT_ERR_BAD_DIM) return 2;
@@ -166,6 +168,12 @@ int main(void) {
         != WHT_ERR_NULL_PTR) return 6;
     if (bwd((void *)16, (void *)16, (float *)16, (void *)16, (float *)16, (float *)16, 4, 1024, 7, NULL, 0, NULL)
         != WHT_ERR_BAD_DTYPE) return 4;
+    /* the static-scratch variant validates the same way, and refuses what its buffer cannot hold */
+    if (bwds(NULL, (void *)16, (float *)16, (void *)16, (float *)16, (float *)16, 4, 1024, WHT_DTYPE_BF16, NULL)
+        != WHT_ERR_NULL_PTR) return 7;
+    if (bwds((void *)16, (void *)16, (float *)16, (void *)16, (float *)16, (float *)16, 4096, 16384, WHT_DTYPE_BF16, NULL)
+        != WHT_ERR_WORKSPACE) return 8;
+    if (wsq(4096, 8192, WHT_DTYPE_BF16) > WHT_STATIC_WORKSPACE_BYTES) return 9;
     if (WHT_MIN_D != 32 || WHT_MAX_D != 16384 || WHT_MIN_D_TWELVE != 768 || WHT_MAX_D_TWELVE != 12288) return 5;
     printf("%s|%d\n", wht_affine_status_string(WHT_OK), wht_affine_version());
     return 0;
