@@ -6,15 +6,15 @@ Two sub-commands:
              known size (the calibration reference for the HBM byte counters), then forward and
              backward a few times -- so that a counter pass (rocprofv3 --pmc ...) stays short:
                  rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT -o fetch -- \
-                     python3 -m paper_2603_08343_amd.profiling drive --workload C5_large
+                     python3 bench_profile.py drive --workload C5_large
   summarize  turn the CSV files of a kernel-trace run and of counter passes into the short text
              summary kept under profiles/ (per-kernel average duration; HBM bytes per launch scaled
              by what the same counter reads for the copy kernel; VALU / MFMA / LDS activity):
-                 python3 -m paper_2603_08343_amd.profiling summarize --workload C5_large \
+                 python3 bench_profile.py summarize --workload C5_large \
                      --kernel-stats OUT/kt/kt_kernel_stats.csv --kernel-trace OUT/kt/kt_kernel_trace.csv \
                      --pmc OUT/*/*_counter_collection.csv
 
-Nothing here is on the product path.
+Nothing here is on the product path (the file sits beside bench.py, outside the package).
 """
 import argparse
 import collections
@@ -31,6 +31,7 @@ NUM_XCD = 8                   # GRBM_GUI_ACTIVE comes back summed over the 8 XCD
 def drive(args):
     import numpy as np
     import torch
+    import bench
     import paper_2603_08343_amd as wht
     from paper_2603_08343_amd import synth
 
@@ -47,7 +48,7 @@ def drive(args):
     dst = torch.empty(COPY_BYTES, dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
     for _ in range(args.steps):
-        wht.wht_affine_copy_baseline(src, dst)
+        bench.bench_copy(torch, src, dst)
     for _ in range(args.steps):
         wht.wht_affine_forward(x, alpha, beta, y=y)
     for _ in range(args.steps):

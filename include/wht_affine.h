@@ -167,14 +167,6 @@ int wht_affine_backward_static(const void *dy, const void *x, const float *alpha
                                void *dx, float *dalpha, float *dbeta,
                                int64_t N, int32_t d, int32_t dtype, void *stream);
 
-/*
- * Measurement aid, not part of the layer: dst[i] = src[i] for `bytes` bytes (a multiple of 16) with
- * the same 16-byte-per-lane access pattern the layer's kernels use.  It gives the benchmark the
- * bandwidth a plain streaming kernel reaches on this GPU and a known-size reference for the
- * profiler's HBM byte counters.  src, dst: device, 16-byte aligned, non-overlapping.
- */
-int wht_affine_copy_baseline(const void *src, void *dst, size_t bytes, void *stream);
-
 /* Static, NUL-terminated description of a wht_status_t (host memory, never freed). */
 const char *wht_affine_status_string(int status);
 

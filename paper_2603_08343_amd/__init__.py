@@ -14,7 +14,6 @@ from .binding import (  # noqa: F401
     wht_affine_backward,
     wht_affine_backward_static,
     wht_affine_backward_workspace_bytes,
-    wht_affine_copy_baseline,
     wht_affine_forward,
     wht_affine_forward_residual,
     wht_affine_forward_residual_stats,

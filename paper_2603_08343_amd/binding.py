@@ -22,7 +22,6 @@ EXPORTS = (
     "wht_affine_backward_workspace_bytes",
     "wht_affine_backward",
     "wht_affine_backward_static",
-    "wht_affine_copy_baseline",
     "wht_affine_status_string",
     "wht_affine_version",
 )
@@ -60,8 +59,6 @@ def library():
         lib.wht_affine_backward.restype = ctypes.c_int
         lib.wht_affine_backward_static.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, vp]
         lib.wht_affine_backward_static.restype = ctypes.c_int
-        lib.wht_affine_copy_baseline.argtypes = [vp, vp, sz, vp]
-        lib.wht_affine_copy_baseline.restype = ctypes.c_int
         lib.wht_affine_status_string.argtypes = [ctypes.c_int]
         lib.wht_affine_status_string.restype = ctypes.c_char_p
         lib.wht_affine_version.argtypes = []
@@ -301,17 +298,3 @@ def wht_affine_backward_static(dy, x, alpha, dx=None, dalpha=None, dbeta=None, s
     if rc != 0:
         raise WhtAffineError(rc, "wht_affine_backward_static")
     return dx, dalpha, dbeta
-
-
-def wht_affine_copy_baseline(src, dst, stream=None):
-    """dst <- src with the kernels' access pattern (measurement aid)."""
-    torch = _torch()
-    nbytes = src.numel() * src.element_size()
-    if dst.numel() * dst.element_size() != nbytes:
-        raise ValueError("src and dst must have the same size in bytes")
-    with torch.cuda.device(src.device):
-        rc = library().wht_affine_copy_baseline(src.data_ptr(), dst.data_ptr(), nbytes,
-                                                _stream_handle(stream, torch, src.device))
-    if rc != 0:
-        raise WhtAffineError(rc, "wht_affine_copy_baseline")
-    return dst

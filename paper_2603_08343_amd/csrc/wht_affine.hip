@@ -335,20 +335,6 @@ int wht_affine_backward_static(const void* dy, const void* x, const float* alpha
     return backward_common(dy, x, alpha, dx, dalpha, dbeta, N, d, dtype, nullptr, 0, true, stream);
 }
 
-int wht_affine_copy_baseline(const void* src, void* dst, size_t bytes, void* stream) {
-    using namespace wht;
-    if (!src || !dst) return WHT_ERR_NULL_PTR;
-    if (bytes % 16 != 0) return WHT_ERR_BAD_DIM;
-    if (!aligned16(src) || !aligned16(dst)) return WHT_ERR_MISALIGNED;
-    if (bytes == 0) return WHT_OK;
-    const size_t nvec = bytes / 16;
-    const size_t want = (nvec + 1023) / 1024;
-    const int grid = (int)(want < (size_t)kNumCU * 64 ? want : (size_t)kNumCU * 64);
-    hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint4*>(src), static_cast<uint4*>(dst), nvec);
-    return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
-}
-
 const char* wht_affine_status_string(int status) {
     switch (status) {
     case WHT_OK:             return "ok";

@@ -398,9 +398,9 @@ __device__ __forceinline__ void unpack_all(float (&r)[C::E], const uint4 (&raw)[
     });
 }
 
-// STREAM: non-temporal stores.  Rows of 12 * 2^m elements are written in 32-byte pieces; in the
-// forward kernel plain stores, which L2 merges into whole lines, measured 17 % faster at d = 6144,
-// in the backward kernel the non-temporal ones stayed ahead.
+// STREAM: non-temporal stores.  Rows of 12 * 2^m elements are written in 32-byte pieces: there
+// plain stores, which L2 merges into whole lines, are used instead (17 % faster in the forward
+// kernel at d = 6144, 6 % in the backward kernel, and no partial-line write traffic).
 template <class C, int PH, bool STREAM = true>
 __device__ __forceinline__ void global_put(const float (&r)[C::E], typename C::io::elem_t* row,
                                            unsigned thread_elem, bool active) {
@@ -843,7 +843,7 @@ __global__ __launch_bounds__(C::BT) void backward_kernel(const typename C::io::e
             for (int i = 0; i < C::E; ++i) g[i] *= a[i];
             transform_back<C, !BOTH>(g, lds, tm, hb, hb2);    // g = H_raw(alpha' dy), first layout
             if (more) wait_vmem<0>();
-            global_put<C, 0>(g, dx + tok * C::kRow, tm.first_elem, active && tm.first_ok);
+            global_put<C, 0, !C::kTwelve>(g, dx + tok * C::kRow, tm.first_elem, active && tm.first_ok);
         } else {
             if (more) wait_vmem<0>();
         }
@@ -1050,7 +1050,7 @@ __global__ __launch_bounds__(3 * C::BT) void backward_teams_kernel(const typenam
             });
             const int64_t tok = wk.token(grp_done);
             const bool active = C::G == 1 || tok < N;
-            global_put<C, 0>(g, dx + tok * C::kRow, tm.first_elem, active && tm.first_ok);
+            global_put<C, 0, !C::kTwelve>(g, dx + tok * C::kRow, tm.first_elem, active && tm.first_ok);
         };
         for (; grp < wk.groups; grp += step) {
             float g[C::E];
@@ -1111,21 +1111,6 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float* __re
 __global__ void zero_kernel(float* a, float* b, int d) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < d) { a[i] = 0.0f; b[i] = 0.0f; }
-}
-
-__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
-                                                   size_t nvec) {
-    // same policy as the layer's kernels: 16 bytes per lane, non-temporal both ways
-    const size_t stride = (size_t)gridDim.x * blockDim.x * 4;
-    for (size_t base = ((size_t)blockIdx.x * blockDim.x) * 4 + threadIdx.x; base < nvec; base += stride) {
-        uint4 v[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if (base + k * 256 < nvec) v[k] = stream_load16(src + base + k * 256);
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if (base + k * 256 < nvec) stream_store16(dst + base + k * 256, v[k]);
-    }
 }
 
 }  // namespace wht
