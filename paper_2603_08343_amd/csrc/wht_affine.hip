@@ -10,6 +10,7 @@
 
 #include "../../include/wht_affine.h"
 #include "wht_device.h"
+#include "wht_validate.h"
 
 namespace wht {
 
@@ -169,23 +170,10 @@ static int dispatch_twelve(int logslots, Op op, Args& a) {
     }
 }
 
-// What a width d is to the library: log2 of the number of slots the schedule runs on, and whether
-// the row is a power of two or 12 * 2^m.
-struct Width { int logd; bool twelve; };
-
 static int dispatch(Width w, int dtype, Op op, Args& a) {
     if (w.twelve) return dispatch_twelve(w.logd, op, a);
     return dtype == WHT_DTYPE_F32 ? dispatch_d<IoF32>(w.logd, op, a) : dispatch_d<IoBF16>(w.logd, op, a);
 }
-
-static int log2_exact(int32_t d) {
-    if (d < 1 || (d & (d - 1)) != 0) return -1;
-    int l = 0;
-    while ((1 << l) < d) ++l;
-    return l;
-}
-
-static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // ------------------------------------------------------------------------------------------------
 // Partial-sum scratch that lives in the library's own code object, for wht_affine_backward_static:
@@ -214,25 +202,6 @@ static void* static_scratch() {
     return scratch_address[dev];
 }
 
-static int check_dims(int64_t N, int32_t d, int32_t dtype, Width* w) {
-    if (dtype != WHT_DTYPE_F32 && dtype != WHT_DTYPE_BF16) return WHT_ERR_BAD_DTYPE;
-    if (N < 0) return WHT_ERR_BAD_DIM;
-    const int l = log2_exact(d);
-    if (l >= 0) {
-        if (d < WHT_MIN_D || d > WHT_MAX_D) return WHT_ERR_BAD_DIM;
-        if (dtype == WHT_DTYPE_F32 && d > WHT_MAX_D_F32) return WHT_ERR_BAD_DIM;
-        *w = Width{l, false};
-        return WHT_OK;
-    }
-    // 12 * 2^m: bfloat16 only, 768 .. 12288
-    if (d % 12 != 0 || dtype != WHT_DTYPE_BF16 || d < WHT_MIN_D_TWELVE || d > WHT_MAX_D_TWELVE)
-        return WHT_ERR_BAD_DIM;
-    const int m = log2_exact(d / 12);
-    if (m < 0) return WHT_ERR_BAD_DIM;
-    *w = Width{m + 4, true};
-    return WHT_OK;
-}
-
 }  // namespace wht
 
 // ------------------------------------------------------------------------------------------------
@@ -244,14 +213,8 @@ static int forward_common(const void* x, const float* alpha, const float* beta, 
                           bool with_resid, void* y, float* sumsq, bool with_stats, int64_t N, int32_t d,
                           int32_t dtype, void* stream) {
     using namespace wht;
-    if (!x || !alpha || !beta || !y || (with_resid && !resid) || (with_stats && !sumsq))
-        return WHT_ERR_NULL_PTR;
     Width w{};
-    if (int rc = check_dims(N, d, dtype, &w)) return rc;
-    if (!aligned16(x) || !aligned16(y) || !aligned16(alpha) || !aligned16(beta) ||
-        (with_resid && !aligned16(resid)) ||
-        (with_stats && (reinterpret_cast<uintptr_t>(sumsq) & 3u) != 0))
-        return WHT_ERR_MISALIGNED;
+    if (int rc = validate_forward(x, alpha, beta, resid, with_resid, y, sumsq, with_stats, N, d, dtype, &w)) return rc;
     if (N == 0) return WHT_OK;
     Args a{};
     a.x = x; a.alpha = alpha; a.beta = beta; a.resid = with_resid ? resid : nullptr; a.y = y; a.N = N;
@@ -293,14 +256,8 @@ static int backward_common(const void* dy, const void* x, const float* alpha, vo
                            size_t workspace_bytes, bool own_scratch, void* stream) {
     using namespace wht;
     const bool grads = dalpha != nullptr || dbeta != nullptr;
-    if (!dy || !alpha) return WHT_ERR_NULL_PTR;
-    if (grads && (!dalpha || !dbeta || !x)) return WHT_ERR_NULL_PTR;   // the two sums come together
-    if (!grads && !dx) return WHT_ERR_NULL_PTR;                        // nothing asked for
     Width w{};
-    if (int rc = check_dims(N, d, dtype, &w)) return rc;
-    if (!aligned16(dy) || !aligned16(x) || !aligned16(alpha) || !aligned16(dx) || !aligned16(dalpha) ||
-        !aligned16(dbeta))
-        return WHT_ERR_MISALIGNED;
+    if (int rc = validate_backward(dy, x, alpha, dx, dalpha, dbeta, N, d, dtype, &w)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (N == 0) {
         if (!grads) return WHT_OK;
@@ -314,8 +271,7 @@ static int backward_common(const void* dy, const void* x, const float* alpha, vo
             workspace = static_scratch();
             if (!workspace) return WHT_ERR_LAUNCH;
         } else {
-            if (!workspace || workspace_bytes < need) return WHT_ERR_WORKSPACE;
-            if (!aligned16(workspace)) return WHT_ERR_MISALIGNED;
+            if (int rc = validate_workspace(workspace, workspace_bytes, need)) return rc;
         }
     }
     Args a{};

@@ -447,7 +447,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 struct HadamardB {
     bf16x8 k_lo, k_hi;      // B operand of the first / second K-half
-    uint32_t minus_first, minus_second;   // bf16 pairs (-1, 0) and (0, -1), see hadamard_round_f32
 };
 
 __device__ __forceinline__ HadamardB make_hadamard_b() {
@@ -467,10 +466,6 @@ __device__ __forceinline__ HadamardB make_hadamard_b() {
     HadamardB b;
     b.k_lo = __builtin_bit_cast(bf16x8, make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]));
     b.k_hi = __builtin_bit_cast(bf16x8, make_uint4(w[1][0], w[1][1], w[1][2], w[1][3]));
-    // Kept opaque to the compiler so that they stay register operands: as an inline constant the
-    // (-1, 0) pair is encoded in a form the bf16 dot instruction reads differently.
-    asm volatile("s_mov_b32 %0, 0xbf80" : "=s"(b.minus_first));
-    asm volatile("s_mov_b32 %0, 0xbf800000" : "=s"(b.minus_second));
     return b;
 }
 
@@ -499,7 +494,7 @@ __device__ __forceinline__ HadamardB make_paley_b(const HadamardB& sylvester) {
             }
             w[half][p] = pair;
         }
-    HadamardB b = sylvester;             // same split selectors
+    HadamardB b = sylvester;
     b.k_lo = __builtin_bit_cast(bf16x8, make_uint4(w[0][0], w[0][1], w[0][2], w[0][3]));
     b.k_hi = __builtin_bit_cast(bf16x8, make_uint4(w[1][0], w[1][1], w[1][2], w[1][3]));
     return b;
@@ -517,18 +512,17 @@ __device__ __forceinline__ f32x16 hadamard_round_bf16(const uint4& a_lo, const u
 
 // One round on float32 data: each value is split into bf16 hi + bf16 lo (hi = RNE(v), lo =
 // RNE(v - hi); v - hi is exact, so |v - hi - lo| <= 2^-18 |v|) and both parts go through the same
-// +-1 product, accumulated in float32.  v - hi is formed without widening hi first: the bf16 dot
-// product  hi.first * (-1) + hi.second * 0 + v  is that difference, exactly.
+// +-1 product, accumulated in float32.  v - hi is formed with plain vector instructions (widen hi by
+// a shift / a mask, subtract): the bf16 dot-product instruction would do it in one, but it executes
+// on the matrix pipeline and stalls behind the rounds' own MFMAs (measured: 20 cycles per dot
+// instruction next to back-to-back MFMAs, against 4.4 alone).
 __device__ __forceinline__ f32x16 hadamard_round_f32(const float* v, const HadamardB& b) {
     uint32_t hi[8], lo[8];
-    const bf16x2 sel0 = __builtin_bit_cast(bf16x2, b.minus_first);
-    const bf16x2 sel1 = __builtin_bit_cast(bf16x2, b.minus_second);
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
         const uint32_t h = IoBF16::pack2(v[2 * p], v[2 * p + 1]);
-        const bf16x2 hp = __builtin_bit_cast(bf16x2, h);
-        const float l0 = __builtin_amdgcn_fdot2_f32_bf16(hp, sel0, v[2 * p], false);
-        const float l1 = __builtin_amdgcn_fdot2_f32_bf16(hp, sel1, v[2 * p + 1], false);
+        const float l0 = v[2 * p] - __uint_as_float(h << 16);
+        const float l1 = v[2 * p + 1] - __uint_as_float(h & 0xffff0000u);
         hi[p] = h;
         lo[p] = IoBF16::pack2(l0, l1);
     }
