@@ -35,7 +35,12 @@ def parse():
     ap.add_argument("--no-extras", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
-    return ap.parse_args()
+    ap.add_argument("--schedule", choices=["default", "butterfly"], default="default",
+                    help="butterfly: force the butterfly schedule for bf16, d >= 1024 (WHT_AFFINE_SCHEDULE)")
+    args = ap.parse_args()
+    if args.schedule == "butterfly":
+        os.environ["WHT_AFFINE_SCHEDULE"] = "butterfly"       # read by the library when it is loaded
+    return args
 
 
 def io_bytes(dtype):
@@ -177,18 +182,39 @@ def summarize(w, step_ms, fwd_ms, bwd_ms):
 _copy_lib = None
 
 
-def bench_copy(torch, src, dst):
-    """dst <- src with the bench-only streaming copy kernel (libwht_copybench.so: 16 bytes per lane,
-    non-temporal both ways; not part of the layer's library)."""
+def _bench_lib():
     global _copy_lib
     if _copy_lib is None:
         from paper_2603_08343_amd.build import COPY_LIB
         _copy_lib = ctypes.CDLL(COPY_LIB)
         _copy_lib.wht_bench_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         _copy_lib.wht_bench_copy.restype = ctypes.c_int
+        _copy_lib.wht_bench_empty.argtypes = [ctypes.c_void_p]
+        _copy_lib.wht_bench_empty.restype = ctypes.c_int
+        _copy_lib.wht_bench_clock_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        _copy_lib.wht_bench_clock_probe.restype = ctypes.c_int
+    return _copy_lib
+
+
+def bench_empty(torch):
+    """One launch of an empty kernel on torch's current stream (the launch path's per-call floor)."""
+    if _bench_lib().wht_bench_empty(torch.cuda.current_stream().cuda_stream) != 0:
+        raise RuntimeError("wht_bench_empty failed")
+
+
+def bench_clock_probe(torch, out):
+    """Enqueue a short probe kernel that writes (shader-clock ticks, 100 MHz ticks) of a fixed spin
+    into out[0:2] (int64 GPU tensor): the shader clock at that point of the stream."""
+    if _bench_lib().wht_bench_clock_probe(out.data_ptr(), torch.cuda.current_stream().cuda_stream) != 0:
+        raise RuntimeError("wht_bench_clock_probe failed")
+
+
+def bench_copy(torch, src, dst):
+    """dst <- src with the bench-only streaming copy kernel (libwht_copybench.so: 16 bytes per lane,
+    non-temporal both ways; not part of the layer's library)."""
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
-    rc = _copy_lib.wht_bench_copy(src.data_ptr(), dst.data_ptr(), nbytes, torch.cuda.current_stream().cuda_stream)
+    rc = _bench_lib().wht_bench_copy(src.data_ptr(), dst.data_ptr(), nbytes, torch.cuda.current_stream().cuda_stream)
     if rc != 0:
         raise RuntimeError(f"wht_bench_copy: status {rc}")
 
@@ -306,14 +332,20 @@ def decode_latency(torch, wht, synth, iters=1000):
         us = a.elapsed_time(e) * 1e3 / iters
         dense = dense_wo(torch, w, iters=200)
         row = {"N": w.N, "d": w.d, "wht_affine_us_per_call": us, "dense_wo_us_per_call": dense["fwd_ms"] * 1e3,
-               "wht_affine_us_per_call_graph": None, "dense_wo_us_per_call_graph": None}
+               "wht_affine_us_per_call_graph": None, "dense_wo_us_per_call_graph": None,
+               "empty_kernel_us_per_call_graph": None, "copy_same_bytes_us_per_call_graph": None}
         try:
             per_graph = 50
             xd = torch.randn(w.N, w.d, device="cuda", dtype=torch.bfloat16)
             Wd = torch.randn(w.d, w.d, device="cuda", dtype=torch.bfloat16) / (w.d ** 0.5)
             bd = torch.zeros(w.d, device="cuda", dtype=torch.bfloat16)
+            yd = torch.empty_like(xd)
             for key, fn in (("wht_affine_us_per_call_graph", lambda: b.fwd(0)),
-                            ("dense_wo_us_per_call_graph", lambda: torch.addmm(bd, xd, Wd.t()))):
+                            ("dense_wo_us_per_call_graph", lambda: torch.addmm(bd, xd, Wd.t())),
+                            # floors of a call on this GPU: a kernel that does nothing, and a plain copy
+                            # of the same x -> y bytes (one memory round trip, no arithmetic)
+                            ("empty_kernel_us_per_call_graph", lambda: bench_empty(torch)),
+                            ("copy_same_bytes_us_per_call_graph", lambda: bench_copy(torch, xd, yd))):
                 side = torch.cuda.Stream()
                 side.wait_stream(torch.cuda.current_stream())
                 with torch.cuda.stream(side):

@@ -1,6 +1,6 @@
 """Helpers around rocprofv3 for the Walsh-Hadamard output layer's kernels.
 
-Two sub-commands:
+Three sub-commands:
 
   drive      launch a short, fixed sequence on one workload -- the plain copy kernel on a buffer of
              known size (the calibration reference for the HBM byte counters), then forward and
@@ -13,6 +13,11 @@ Two sub-commands:
                  python3 bench_profile.py summarize --workload C5_large \
                      --kernel-stats OUT/kt/kt_kernel_stats.csv --kernel-trace OUT/kt/kt_kernel_trace.csv \
                      --pmc OUT/*/*_counter_collection.csv
+
+  series     the first steps of forward + backward after the GPU has idled, each step timed with
+             events and followed by a probe of the shader clock: shows the clock transient that a
+             short benchmark run sits in
+                 python3 bench_profile.py series --workload C5_large --steps 80
 
 Nothing here is on the product path (the file sits beside bench.py, outside the package).
 """
@@ -29,6 +34,9 @@ NUM_XCD = 8                   # GRBM_GUI_ACTIVE comes back summed over the 8 XCD
 
 
 def drive(args):
+    import os
+    if args.schedule == "butterfly":
+        os.environ["WHT_AFFINE_SCHEDULE"] = "butterfly"       # read by the library when it is loaded
     import numpy as np
     import torch
     import bench
@@ -57,6 +65,54 @@ def drive(args):
     print(f"drove {args.steps} x (copy 1 GiB, forward, backward) on {w.name}", flush=True)
 
 
+def series(args):
+    """fwd+bwd steps from an idle GPU: per step the two entry points' times (events) and the shader
+    clock right after the step (probe kernel: shader-clock ticks per 100 MHz tick)."""
+    import time
+    import torch
+    import bench
+    import paper_2603_08343_amd as wht
+    from paper_2603_08343_amd import synth
+
+    w = synth.WORKLOADS[args.workload]
+    b = bench.Bench(torch, wht, synth, args.workload)
+    K = args.steps
+    probes = torch.zeros(K, 2, dtype=torch.int64, device="cuda")
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    torch.cuda.synchronize()
+    time.sleep(args.idle)
+    for i in range(K):
+        ev[i][0].record()
+        b.fwd(i)
+        ev[i][1].record()
+        if w.backward:
+            b.bwd(i)
+        ev[i][2].record()
+        bench.bench_clock_probe(torch, probes[i])
+    torch.cuda.synchronize()
+    p = probes.cpu().numpy()
+    print(f"workload {w.name}: N={w.N} d={w.d} {w.dtype} I/O; {K} steps after {args.idle} s of idling")
+    print("step  fwd_us  bwd_us  shader_MHz")
+    rows = []
+    for i in range(K):
+        f = ev[i][0].elapsed_time(ev[i][1]) * 1e3
+        g = ev[i][1].elapsed_time(ev[i][2]) * 1e3 if w.backward else 0.0
+        mhz = 100.0 * p[i][0] / max(1, p[i][1])
+        rows.append((f, g, mhz))
+        print(f"{i:4d} {f:7.1f} {g:7.1f} {mhz:8.0f}")
+    lo, hi = 5, min(K, 25)
+    print(f"mean of steps {lo}..{hi - 1} (the window a run with 5 warm-up and 20 timed steps sees): "
+          f"fwd {sum(r[0] for r in rows[lo:hi]) / (hi - lo):.1f} us, bwd {sum(r[1] for r in rows[lo:hi]) / (hi - lo):.1f} us, "
+          f"clock {sum(r[2] for r in rows[lo:hi]) / (hi - lo):.0f} MHz (min {min(r[2] for r in rows[lo:hi]):.0f})")
+    t = rows[max(0, K - 20):]
+    print(f"mean of the last {len(t)} steps: fwd {sum(r[0] for r in t) / len(t):.1f} us, bwd {sum(r[1] for r in t) / len(t):.1f} us, "
+          f"clock {sum(r[2] for r in t) / len(t):.0f} MHz")
+
+
+def _ours(name: str) -> bool:
+    return "wht::" in name or "copy_kernel" in name
+
+
 def _short(name: str) -> str:
     name = name.replace("void wht::", "").replace("wht::", "")
     return name.split("(")[0].strip()
@@ -66,14 +122,15 @@ def summarize(args):
     from paper_2603_08343_amd import synth
     w = synth.WORKLOADS[args.workload]
     s = 2 if w.dtype == "bf16" else 4
-    algo = {"forward_kernel": 2 * w.N * w.d * s + 8 * w.d, "backward_kernel": 3 * w.N * w.d * s + 12 * w.d}
+    algo = {"forward_kernel": 2 * w.N * w.d * s + 8 * w.d, "backward_kernel": 3 * w.N * w.d * s + 12 * w.d,
+            "backward_teams_kernel": 3 * w.N * w.d * s + 12 * w.d}
     out = [f"workload {w.name}: N={w.N} d={w.d} {w.dtype} I/O"]
 
     if args.kernel_stats:
         out.append("")
         out.append("kernel-trace --stats (ns): name, calls, average, min, max, % of GPU time")
         for row in csv.DictReader(open(args.kernel_stats)):
-            if "wht::" in row["Name"]:
+            if _ours(row["Name"]):
                 out.append(f"  {_short(row['Name']):48s} calls {row['Calls']:>5s}  avg {float(row['AverageNs']):10.0f}"
                            f"  min {row['MinNs']:>8s}  max {row['MaxNs']:>8s}  {row['Percentage']}%")
 
@@ -82,7 +139,7 @@ def summarize(args):
         # untimed warm-up, during which the clocks are still settling
         per_kernel = collections.defaultdict(list)
         for row in csv.DictReader(open(args.kernel_trace)):
-            if "wht::" in row["Kernel_Name"]:
+            if _ours(row["Kernel_Name"]):
                 per_kernel[_short(row["Kernel_Name"])].append(
                     (int(row["Start_Timestamp"]), int(row["End_Timestamp"]) - int(row["Start_Timestamp"])))
         out.append("")
@@ -97,7 +154,7 @@ def summarize(args):
     for pattern in args.pmc or []:
         for path in glob.glob(pattern):
             for row in csv.DictReader(open(path)):
-                if "wht::" not in row["Kernel_Name"]:
+                if not _ours(row["Kernel_Name"]):
                     continue
                 k = _short(row["Kernel_Name"])
                 counters[k][row["Counter_Name"]].append(float(row["Counter_Value"]))
@@ -159,7 +216,13 @@ def main():
     d = sub.add_parser("drive")
     d.add_argument("--workload", default="C5_large")
     d.add_argument("--steps", type=int, default=3)
+    d.add_argument("--schedule", choices=["default", "butterfly"], default="default")
     d.set_defaults(fn=drive)
+    c = sub.add_parser("series")
+    c.add_argument("--workload", default="C5_large")
+    c.add_argument("--steps", type=int, default=80)
+    c.add_argument("--idle", type=float, default=1.0, help="seconds of idling before the first step")
+    c.set_defaults(fn=series)
     s = sub.add_parser("summarize")
     s.add_argument("--workload", default="C5_large")
     s.add_argument("--kernel-stats")

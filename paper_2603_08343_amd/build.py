@@ -12,6 +12,10 @@ LIB = os.path.join(HERE, "libwht_affine.so")
 # bench-only object (a plain copy kernel): not part of the layer's ABI, never loaded by the binding
 COPY_SRC = os.path.join(HERE, "csrc", "copy_bench.hip")
 COPY_LIB = os.path.join(HERE, "libwht_copybench.so")
+# debug build of the layer's library for one GPU test: after every LDS read the thread overwrites
+# what it read with NaN, so that a read that comes before its data (a missing barrier or wait) shows
+# up as NaN; carries the widths 512, 4096, 8192, 16384 and 6144 only
+POISON_LIB = os.path.join(HERE, "libwht_affine_poison.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -29,6 +33,7 @@ SOURCES = [SRC] + [os.path.join(HERE, "csrc", f) for f in ("wht_device.h", "wht_
 
 def build(verbose: bool = False, extra=()) -> str:
     _compile(COPY_SRC, COPY_LIB, verbose, extra)
+    _compile(SRC, POISON_LIB, verbose, (*extra, "-DWHT_POISON_LDS"))
     return _compile(SRC, LIB, verbose, extra)
 
 
@@ -50,9 +55,10 @@ def _compile(src: str, lib: str, verbose: bool, extra=()) -> str:
 def ensure_built(verbose: bool = False) -> str:
     """For harnesses (tests, smoke check, benchmark): compile only if nothing has been built yet.
     The binding itself never builds: a missing library is an error there."""
-    if not os.path.exists(LIB) or not os.path.exists(COPY_LIB):
+    if not os.path.exists(LIB) or not os.path.exists(COPY_LIB) or not os.path.exists(POISON_LIB):
         build(verbose=verbose)
-    elif any(os.path.getmtime(f) > os.path.getmtime(LIB) for f in SOURCES if os.path.exists(f)):
+    elif any(os.path.getmtime(f) > min(os.path.getmtime(LIB), os.path.getmtime(POISON_LIB))
+             for f in SOURCES if os.path.exists(f)):
         # a stale binary would be validated and recorded under the new sources' name
         raise RuntimeError(f"{LIB} is older than its sources: run `python -m paper_2603_08343_amd.build`")
     return LIB

@@ -1,7 +1,8 @@
 // Bench-only shared object (libwht_copybench.so), not part of the layer's C ABI: a plain streaming
-// copy with the access pattern of the layer's kernels (16 bytes per lane, non-temporal both ways).
-// The benchmark uses it as the bandwidth a streaming kernel reaches on this GPU, and the profiling
-// helper as a known-size reference for the profiler's HBM byte counters.
+// copy with the access pattern of the layer's kernels (16 bytes per lane, non-temporal both ways)
+// and an empty kernel.  The benchmark uses the copy as the bandwidth a streaming kernel reaches on
+// this GPU and, at the decode shapes, both as the latency floor of a call; the profiling helper
+// uses the copy as a known-size reference for the profiler's HBM byte counters.
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -19,6 +20,30 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src
         for (int k = 0; k < 4; ++k)
             if (base + k * 256 < nvec) __builtin_nontemporal_store(v[k], dst + base + k * 256);
     }
+}
+
+__global__ void empty_kernel() {}
+
+// One launch of a kernel that does nothing: the per-call floor of the launch path on `stream`.
+extern "C" int wht_bench_empty(void* stream) {
+    hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream));
+    return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+// Shader clock now: counts of the shader-clock counter and of the constant 100 MHz counter over a
+// short spin, written to out[0], out[1] (device memory, two uint64).  MHz = 100 * out[0] / out[1].
+__global__ void clock_probe_kernel(unsigned long long* out) {
+    const unsigned long long c0 = clock64(), r0 = wall_clock64();
+    float v = (float)threadIdx.x;
+    for (int i = 0; i < 2000; ++i) v = v * 1.0001f + 0.5f;
+    const unsigned long long c1 = clock64(), r1 = wall_clock64();
+    if (threadIdx.x == 0) { out[0] = c1 - c0 + (v == 12345.678f); out[1] = r1 - r0; }
+}
+extern "C" int wht_bench_clock_probe(void* out, void* stream) {
+    if (!out) return 1;
+    hipLaunchKernelGGL(clock_probe_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream),
+                       static_cast<unsigned long long*>(out));
+    return hipGetLastError() == hipSuccess ? 0 : 2;
 }
 
 // dst[i] = src[i] for `bytes` bytes (a multiple of 16); device pointers, 16-byte aligned, not

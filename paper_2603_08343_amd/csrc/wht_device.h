@@ -216,6 +216,17 @@ __device__ __forceinline__ void run_stages(float (&r)[C::E]) {
     });
 }
 
+// Debug build (WHT_POISON_LDS, used by csrc/poison_check.hip only): a thread that has read its
+// values from an exchange region or from its own stage slot overwrites them with NaN.  A read that
+// comes too early -- before the data it is meant to see has been written or has landed, i.e. a
+// missing barrier or a missing wait -- then returns NaN instead of last iteration's plausible
+// values, and the comparison against the oracle fails loudly.
+#ifdef WHT_POISON_LDS
+constexpr bool kPoisonLds = true;
+#else
+constexpr bool kPoisonLds = false;
+#endif
+
 template <class C, int PH>
 constexpr bool phase_is_vec4() { return C::plan.ph[PH].rb[0] == 0 && C::plan.ph[PH].rb[1] == 1; }
 
@@ -252,6 +263,14 @@ __device__ __forceinline__ void lds_get(float (&r)[C::E], const float* tok) {
             constexpr int I = decltype(i)::value;
             constexpr unsigned off = C::phys(reg_elem_offset(C::plan.ph[PH], C::e, I));
             r[I] = tok[off];
+        });
+    }
+    if constexpr (kPoisonLds) {
+        const float nan = __uint_as_float(0x7fc00000u);
+        static_for<0, C::E>([&](auto i) {
+            constexpr int I = decltype(i)::value;
+            constexpr unsigned off = C::phys(reg_elem_offset(C::plan.ph[PH], C::e, I));
+            const_cast<float*>(tok)[off] = nan;
         });
     }
 }
@@ -351,7 +370,9 @@ __device__ __forceinline__ unsigned lds_byte_address(const void* p) {
     return (unsigned)(size_t)(const __attribute__((address_space(3))) unsigned char*)p;
 }
 
-template <class C>
+//   OWN: the slot was filled by this wave's own loads and nobody else reads it (poisoned after the
+//   read in the debug build); false for a slot that another wave fetched or also reads.
+template <class C, bool OWN = true>
 __device__ __forceinline__ void stage_read(uint4 (&raw)[C::NV], const unsigned char* wave_slot) {
     static_assert(C::NV == 1 || C::NV == 2 || C::NV == 4 || C::NV == 8, "unexpected vector count");
     const unsigned addr = lds_byte_address(wave_slot) + (threadIdx.x & 63u) * 16u;
@@ -373,6 +394,15 @@ __device__ __forceinline__ void stage_read(uint4 (&raw)[C::NV], const unsigned c
                      : : "memory");
 #pragma unroll
     for (int c = 0; c < C::NV; ++c) raw[c] = make_uint4(v[c].x, v[c].y, v[c].z, v[c].w);
+    if constexpr (kPoisonLds && OWN) {
+        const u32x4 nan = {0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u};   // NaN as bf16 pairs and as f32
+#pragma unroll
+        for (int c = 0; c < C::NV; ++c) {
+            const unsigned a = addr + c * 1024;
+            asm volatile("ds_write_b128 %0, %1" : : "v"(a), "v"(nan) : "memory");
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
 }
 
 // Padding lanes of a 12 * 2^m row read stale LDS: replace it by zeros (the padding's value).
@@ -974,7 +1004,7 @@ __global__ __launch_bounds__(3 * C::BT) void backward_teams_kernel(const typenam
             lds_put<C, 0>(r, lds_x + tm.lds_off[0]);
             exchange_barrier();                                 // B1(k)
             lds_get<C, LAST>(r, lds_x + tm.lds_off[LAST]);
-            stage_read<C>(graw, par ? stage_g1 : stage_g0);
+            stage_read<C, false>(graw, par ? stage_g1 : stage_g0);     // fetched by the Y1 waves, read by both
             zero_padding<C>(graw, tm.last_ok);
             run_stages<C, LAST>(r);
             unpack_all<C>(g, graw);
@@ -999,7 +1029,7 @@ __global__ __launch_bounds__(3 * C::BT) void backward_teams_kernel(const typenam
             const bool more = grp + step < wk.groups;
             uint4 graw[C::NV];
             wait_vmem<0>();                                     // dy(k) has landed
-            stage_read<C>(graw, par ? stage_g1 : stage_g0);
+            stage_read<C, false>(graw, par ? stage_g1 : stage_g0);
             zero_padding<C>(graw, tm.last_ok);
             if (more) stage_issue<C, LAST>(par ? stage_g0 : stage_g1, dy + wk.row(grp + step) * C::kRow, tm.last_elem, tm.last_ok);
             float g[C::E];

@@ -46,6 +46,8 @@ WORKLOADS = {w.name: w for w in [
     Workload("W_tiny_768", 32 * 1024, 768, "bf16", True, note="Table 2 Tiny: 12 heads x 64, B=32 S=1024"),
     Workload("W_base_1536", 32 * 1024, 1536, "bf16", True, note="Table 2 Base: 16 heads x 96, B=32 S=1024"),
     Workload("W_wide_6144", 4 * 8192, 6144, "bf16", True, note="48 heads x 128, B=4 S=8192"),
+    # float32 I/O at a bandwidth-bound size: the butterfly schedule's kernels
+    Workload("F32_4096", 16384, 4096, "f32", True, note="float32 tensors, 32 heads x 128, B=4 S=4096"),
 ]}
 
 
