@@ -37,6 +37,14 @@
  *   - x, y, dy, dx are row-major [N, d], contiguous (leading dimension d), of type `dtype`.
  *     alpha, beta, dalpha, dbeta are float32 [d] whatever `dtype` is.
  *   - bfloat16 tensors are computed in float32 internally and rounded to nearest-even on store.
+ *     For bfloat16 tensors of d >= 1024 (and all 12 * 2^m widths) ten of the log2(d) stages run on
+ *     the matrix cores as products with +-1 matrices: exact products, float32 accumulation, and a
+ *     float32 value entering such a product is represented as the sum of two bfloat16 terms, which
+ *     carries it to a relative error of at most 2^-18 (three orders of magnitude below the bfloat16
+ *     output's own rounding).  float32 tensors never take this path.
+ *   - Non-finite inputs: NaN propagates.  An infinite input makes the token's outputs +-Inf or NaN
+ *     with float32 tensors (Inf - Inf in a butterfly) and NaN with bfloat16 tensors of d >= 1024
+ *     (the two-term representation of Inf is Inf + NaN).
  *   - All tensor pointers must be 16-byte aligned.  y may alias x exactly, dx may alias dy or x
  *     exactly; partial overlap is undefined.
  *   - The return value is a wht_status_t.  Arguments are validated before anything is enqueued, so

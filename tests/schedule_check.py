@@ -3,7 +3,7 @@ library reads WHT_AFFINE_SCHEDULE once per process.  Used by test_gpu_schedules.
 
     WHT_AFFINE_SCHEDULE=butterfly python tests/schedule_check.py
 
-Checks forward and backward against the CPU oracle for bf16 at d = 1024 ... 8192 with ragged token
+Checks forward and backward against the CPU oracle for bf16 at d = 1024 ... 16384 with ragged token
 counts, to the same tolerances as tests/test_gpu_parity.py.  Exit status 0 iff everything passes."""
 import os
 import sys
@@ -20,7 +20,7 @@ from parity import assert_grad_close, assert_io_close, to_gpu  # noqa: E402
 
 
 def main():
-    for d, N in ((1024, 263), (2048, 131), (4096, 67), (8192, 1031)):
+    for d, N in ((1024, 263), (2048, 131), (4096, 67), (8192, 1031), (16384, 35)):
         inp = synth.make_inputs(N, d, "bf16", seed=100 + d)
         print(f"[schedule_check] {os.environ.get('WHT_AFFINE_SCHEDULE', 'default')} d={d} N={N}", flush=True)
         x, dy = to_gpu(inp.x, "bf16"), to_gpu(inp.dy, "bf16")

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 def test_butterfly_schedule_bf16_large_d():
     env = dict(os.environ, WHT_AFFINE_SCHEDULE="butterfly")
-    print("[parity] butterfly schedule, bf16, d = 1024..8192 (child process)", flush=True)
+    print("[parity] butterfly schedule, bf16, d = 1024..16384 (child process)", flush=True)
     out = subprocess.run([sys.executable, os.path.join(HERE, "schedule_check.py")], env=env,
                          capture_output=True, text=True, timeout=280)
     assert out.returncode == 0, out.stdout[-2000:] + out.stderr[-2000:]
