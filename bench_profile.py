@@ -110,7 +110,7 @@ def series(args):
 
 
 def _ours(name: str) -> bool:
-    return "wht::" in name or "copy_kernel" in name
+    return "wht::" in name or name.startswith(("copy_kernel", "void copy_kernel"))
 
 
 def _short(name: str) -> str:
@@ -122,7 +122,8 @@ def summarize(args):
     from paper_2603_08343_amd import synth
     w = synth.WORKLOADS[args.workload]
     s = 2 if w.dtype == "bf16" else 4
-    algo = {"forward_kernel": 2 * w.N * w.d * s + 8 * w.d, "backward_kernel": 3 * w.N * w.d * s + 12 * w.d,
+    algo = {"forward_kernel": 2 * w.N * w.d * s + 8 * w.d, "forward_once_kernel": 2 * w.N * w.d * s + 8 * w.d,
+            "backward_kernel": 3 * w.N * w.d * s + 12 * w.d,
             "backward_teams_kernel": 3 * w.N * w.d * s + 12 * w.d}
     out = [f"workload {w.name}: N={w.N} d={w.d} {w.dtype} I/O"]
 

@@ -772,6 +772,62 @@ __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::el
     }
 }
 
+// One 16-byte vector per NV of a row, in the layout of phase PH, straight into registers (cached
+// load).  Padding lanes of a 12 * 2^m row read the row's first block instead (in bounds) and hold zeros.
+template <class C, int PH>
+__device__ __forceinline__ void global_get(uint4 (&raw)[C::NV], const typename C::io::elem_t* row,
+                                           unsigned thread_elem, bool ok) {
+    const unsigned base = (!C::kTwelve || ok) ? thread_elem : 0u;
+    static_for<0, C::NV>([&](auto c) {
+        constexpr int Cc = decltype(c)::value;
+        constexpr unsigned off = C::real(reg_elem_offset(C::plan.ph[PH], C::e, Cc * C::V));
+        raw[Cc] = *reinterpret_cast<const uint4*>(row + base + off);
+    });
+    zero_padding<C>(raw, ok);
+}
+
+// forward for a few tokens (decoding, paper Sec. 5: one token per sequence and step): one token
+// group per workgroup and nothing else.  With so little work a launch is one memory round trip
+// long, so everything the group needs -- x, alpha, beta, the residual -- is requested at once,
+// straight into registers, before anything is awaited; there is no token loop, no prefetch stage and
+// no walk over the grid, whose set-up costs the persistent kernel about a microsecond per launch.
+template <class C, bool RESID>
+__global__ __launch_bounds__(C::BT) void forward_once_kernel(const typename C::io::elem_t* x,
+                                                             const float* __restrict__ alpha,
+                                                             const float* __restrict__ beta,
+                                                             const typename C::io::elem_t* resid,
+                                                             typename C::io::elem_t* y, int64_t N) {
+    __shared__ __align__(16) float lds[C::kExchangeBytes / 4];
+    constexpr int LAST = C::P - 1;
+    const unsigned t = threadIdx.x % C::TPT, slot = threadIdx.x / C::TPT;
+    ThreadMap<C> tm;
+    tm.init(t, slot);
+    const int64_t tok = (int64_t)blockIdx.x * C::G + slot;
+    const int64_t row = tok < N ? tok : N - 1;                  // a ragged group re-reads the last token
+    uint4 raw[C::NV], rraw[RESID ? C::NV : 1];
+    global_get<C, 0>(raw, x + row * C::kRow, tm.first_elem, tm.first_ok);
+    if constexpr (RESID) global_get<C, LAST>(rraw, resid + row * C::kRow, tm.last_elem, tm.last_ok);
+    float a[C::E], b[C::E];
+    param_get<C, LAST>(a, alpha, tm.last_elem, tm.last_ok, inv_sqrt_d<C>());
+    param_get<C, LAST>(b, beta, tm.last_elem, tm.last_ok, 1.0f);
+    HadamardB hb{}, hbp{};
+    if constexpr (C::kMfma) hb = make_hadamard_b();
+    if constexpr (C::kTwelve) hbp = make_paley_b(hb);
+    const HadamardB& hb2 = C::kTwelve ? hbp : hb;
+    float r[C::E];
+    transform_from_raw<C, false>(r, raw, lds, tm, hb, hb2);
+    if constexpr (RESID) {
+        float res[C::E];
+        unpack_all<C>(res, rraw);
+#pragma unroll
+        for (int i = 0; i < C::E; ++i) r[i] = res[i] + fmaf(r[i], a[i], b[i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < C::E; ++i) r[i] = fmaf(r[i], a[i], b[i]);
+    }
+    global_put<C, LAST, false>(r, y + tok * C::kRow, tm.last_elem, tok < N && tm.last_ok);
+}
+
 // backward:  z = H x (recomputed);  dalpha += dy z;  dbeta += dy;  dx = H_raw((alpha/sqrt d) dy)
 // Each workgroup keeps its dalpha/dbeta sums in registers and at the end writes one row of partial
 // sums; reduce_partials_kernel adds the rows in a fixed order, so the result does not depend on

@@ -193,6 +193,10 @@ constexpr int mfma_log_tiles(int logd, bool backward) {
     return logd <= 10 ? 0 : ((logd >= 14 && !backward) ? 2 : 1);
 }
 
+// For a few tokens per launch (one token group per workgroup): as few tiles per wave as the schedule
+// allows, i.e. as many waves per token, which shortens each wave's chain of dependent instructions.
+constexpr int mfma_log_tiles_few(int logd) { return logd <= 12 ? 0 : 1; }
+
 // ---- rows of 12 * 2^m elements on 2^n = 16 * 2^m slots ----------------------------------------
 // Slot index s = (r_hi << 8) | (b << 4) | r_lo  <->  element b * 2^m + (r_hi << 4 | r_lo), m = n - 4:
 // the block number b = 0..11 occupies slot bits 4..7, b = 12..15 are padding.  A bit permutation, so
@@ -204,11 +208,22 @@ constexpr bool twelve_valid(unsigned s) { return ((s >> 6) & 3u) != 3u; }
 
 // P12: symmetric order-12 Hadamard matrix (Paley's second construction over GF(5)), first row and
 // column +1.  Bit c of row r's mask is set where P12[r][c] = -1.
+// The twelve masks 0x000 0x556 0x3ca 0x96c 0xf22 0x5b8 0xc8e 0x6e4 0x23e 0xb94 0x8f2 0xe58 are packed
+// five to a 64-bit word and picked out with shifts: on the GPU a table indexed at run time would be
+// a memory load, and the kernels build their matrix operand from this on every launch.
 constexpr unsigned paley12_minus_row(unsigned r) {
+    const unsigned long long word = r < 5u ? 0x0f2296c3ca556000ull : (r < 10u ? 0x0b9423e6e4c8e5b8ull : 0xe588f2ull);
+    const unsigned k = r < 5u ? r : (r < 10u ? r - 5u : r - 10u);
+    return (unsigned)(word >> (12u * k)) & 0xfffu;
+}
+constexpr bool paley12_packing_matches() {
     constexpr unsigned rows[12] = {0x000, 0x556, 0x3ca, 0x96c, 0xf22, 0x5b8,
                                    0xc8e, 0x6e4, 0x23e, 0xb94, 0x8f2, 0xe58};
-    return rows[r];
+    for (unsigned r = 0; r < 12u; ++r)
+        if (paley12_minus_row(r) != rows[r]) return false;
+    return true;
 }
+static_assert(paley12_packing_matches(), "packed P12 masks");
 // Entry of the matrix the second matrix-core round applies along slot bits 3..7 of such a row:
 // index m = bit3 + 2 * block;  (-1)^(bit3_in & bit3_out) * P12[block_in][block_out], 0 on padding.
 constexpr int twelve_round_entry(unsigned m_in, unsigned m_out) {

@@ -195,13 +195,66 @@ def test_forward_clustered_deal_with_ragged_regions(N):
 
 def test_many_passes_per_workgroup():
     # more token groups than the grid cap: every workgroup loops several times, last pass ragged
-    inp = synth.make_inputs(5000, 256, "bf16", seed=3)
-    _announce("grid-stride d=256 N=5000 (tokens per workgroup 32, 157 groups)")
+    inp = synth.make_inputs(70005, 256, "bf16", seed=3)
+    _announce("grid-stride d=256 N=70005 (tokens per workgroup 32, 2188 groups)")
     check_forward_full(inp, "fwd strided")
-    inp2 = synth.make_inputs(40001, 64, "f32", seed=4)
-    _announce("grid-stride d=64 N=40001")
+    inp2 = synth.make_inputs(140001, 64, "f32", seed=4)
+    _announce("grid-stride d=64 N=140001")
     check_forward_full(inp2, "fwd strided d=64")
     check_backward_full(inp2, "bwd strided d=64")
+
+
+# ------------------------------------------------------------------ few tokens per call (decoding)
+#
+# Calls of up to FEW_TOKEN_ELEMS elements (half that for d = 12 * 2^m) run on a kernel of their own:
+# one token group per workgroup, no token loop.  The small cases above pass through it; the cases
+# here pin the decode shapes of the paper's Table 2 widths, the hand-over to the persistent kernel
+# and that kernel just above the limit, where it has the fewest passes per workgroup.
+
+FEW_TOKEN_ELEMS = 1 << 22
+
+
+def _few_token_limit(d):
+    return (FEW_TOKEN_ELEMS // 2 if d % 3 == 0 else FEW_TOKEN_ELEMS) // d
+
+
+@pytest.mark.parametrize("N", [1, 16, 64, 256])
+@pytest.mark.parametrize("d,dtype", [(768, "bf16"), (1024, "bf16"), (1536, "bf16"), (2048, "bf16"), (4096, "bf16"),
+                                     (8192, "bf16"), (16384, "bf16"), (12288, "bf16"), (512, "bf16"),
+                                     (256, "f32"), (4096, "f32")])
+def test_forward_few_tokens(d, dtype, N):
+    _announce(f"few tokens: forward and forward+residual d={d} {dtype} N={N}")
+    inp = synth.make_inputs(N, d, dtype, seed=3 * d + N)      # dy doubles as the residual stream
+    x, resid = to_gpu(inp.x, dtype), to_gpu(inp.dy, dtype)
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    # one row more than the call may touch: it must keep its NaN fill
+    buf, bufr = nan_filled(N + 1, d, dtype), nan_filled(N + 1, d, dtype)
+    y = wht.wht_affine_forward(x, a, b, y=buf[:N])
+    yr = wht.wht_affine_forward_residual(x, a, b, resid, y=bufr[:N])
+    torch.cuda.synchronize()
+    assert_io_close(y, oracle.forward(inp.x, inp.alpha, inp.beta, _method(d)), dtype, f"few d={d} N={N} y")
+    assert_io_close(yr, oracle.forward_residual(inp.x, inp.alpha, inp.beta, inp.dy, _method(d)), dtype,
+                    f"few d={d} N={N} y+resid")
+    assert bool(torch.isnan(buf[N].float()).all()) and bool(torch.isnan(bufr[N].float()).all())
+
+
+@pytest.mark.parametrize("d,dtype", [(d, "bf16") for d in ALL_D + TWELVE_D] + [(d, "f32") for d in ALL_D[:-1]])
+def test_forward_on_both_sides_of_the_few_token_limit(d, dtype):
+    # N = limit runs the one-pass kernel, N = limit + 37 the persistent one (ragged last group): both
+    # against the oracle, and bit for bit against each other on the rows they share.
+    lim = _few_token_limit(d)
+    N = lim + 37
+    _announce(f"few-token limit d={d} {dtype}: N={lim} and N={N}")
+    inp = synth.make_inputs(N, d, dtype, seed=d + 11, backward=False)
+    x = to_gpu(inp.x, dtype)
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    y_few = wht.wht_affine_forward(x[:lim], a, b, y=nan_filled(lim, d, dtype))
+    y_all = wht.wht_affine_forward(x, a, b, y=nan_filled(N, d, dtype))
+    torch.cuda.synchronize()
+    bits = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(y_few.view(bits), y_all[:lim].view(bits))
+    _assert_all_tokens(y_all, lambda lo, hi: oracle.forward(inp.x[lo:hi], inp.alpha, inp.beta, "fast"),
+                       N, dtype, f"limit d={d} y")
 
 
 # ------------------------------------------------------------------ residual add fused into the epilogue
