@@ -101,13 +101,14 @@ class Bench:
 
     def run(self, steps, warmup):
         """Times `steps` whole steps (wall clock between synchronisations) and, inside the same
-        region, every forward and backward launch with events on the launch stream."""
+        region, every forward and backward call with events on the launch stream (StreamEvent: an
+        event record is itself a few microseconds of stream time, which the step time includes)."""
         torch = self.torch
         for i in range(warmup):
             self.fwd(i)
             if self.w.backward:
                 self.bwd(i)
-        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        ev = [[StreamEvent(torch) for _ in range(3)] for _ in range(steps)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
@@ -123,6 +124,28 @@ class Bench:
         bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps if self.w.backward else None
         return (t1 - t0) * 1e3 / steps, fwd_ms, bwd_ms
 
+    def series(self, calls=50, warmup=5):
+        """Per-call time of each entry point called back to back, `calls` times between one pair of
+        events: no event between the launches, so this is what a caller that does not time single
+        launches sees.  Returns (fwd_ms, bwd_ms or None)."""
+        torch = self.torch
+        out = []
+        for fn in (self.fwd, self.bwd if self.w.backward else None):
+            if fn is None:
+                out.append(None)
+                continue
+            for i in range(warmup):
+                fn(i)
+            a, b = StreamEvent(torch), StreamEvent(torch)
+            torch.cuda.synchronize()
+            a.record()
+            for i in range(calls):
+                fn(i)
+            b.record()
+            torch.cuda.synchronize()
+            out.append(a.elapsed_time(b) / calls)
+        return tuple(out)
+
 
 def paper_protocol(bench, runs=3, iters=50, warmup=10):
     """The paper's timing protocol (Sec. 5, captions of Tables 4 and 5: mean and standard deviation
@@ -135,7 +158,7 @@ def paper_protocol(bench, runs=3, iters=50, warmup=10):
             bench.bwd(i)
     per_run = {"fwd": [], "bwd": [], "step": []}
     for _ in range(runs):
-        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(iters)]
+        ev = [[StreamEvent(torch) for _ in range(3)] for _ in range(iters)]
         torch.cuda.synchronize()
         for i in range(iters):
             ev[i][0].record()
@@ -159,6 +182,31 @@ def paper_protocol(bench, runs=3, iters=50, warmup=10):
     out["step_ms_mean"] = statistics.mean(per_run["step"])
     out["step_ms_std"] = statistics.stdev(per_run["step"])
     out["tokens_per_s"] = w.N / (out["step_ms_mean"] * 1e-3)
+    return out
+
+
+def add_series(row, w, fwd_ms, bwd_ms):
+    """Back-to-back per-call times (Bench.series) into a workload's summary row."""
+    row["fwd_ms_back_to_back"] = round(fwd_ms, 5)
+    row["fwd_frac_hbm_peak_back_to_back"] = algorithmic_bytes(w.N, w.d, w.dtype, "fwd") / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+    if bwd_ms is not None:
+        row["bwd_ms_back_to_back"] = round(bwd_ms, 5)
+        row["bwd_frac_hbm_peak_back_to_back"] = algorithmic_bytes(w.N, w.d, w.dtype, "bwd") / (bwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+
+
+def event_cost(torch, n=200):
+    """Microseconds between two consecutive event records with nothing between them: what one
+    record costs on the stream, for the events this benchmark uses and for torch.cuda.Event."""
+    out = {}
+    for key, make in (("stream_event_us", lambda: StreamEvent(torch)),
+                      ("torch_event_us", lambda: torch.cuda.Event(enable_timing=True))):
+        ev = [make() for _ in range(n)]
+        torch.cuda.synchronize()
+        for e in ev:
+            e.record()
+        torch.cuda.synchronize()
+        gaps = [ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(n // 4, n - 1)]
+        out[key] = sum(gaps) / len(gaps)
     return out
 
 
@@ -193,7 +241,43 @@ def _bench_lib():
         _copy_lib.wht_bench_empty.restype = ctypes.c_int
         _copy_lib.wht_bench_clock_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
         _copy_lib.wht_bench_clock_probe.restype = ctypes.c_int
+        _copy_lib.wht_bench_event_create.argtypes = []
+        _copy_lib.wht_bench_event_create.restype = ctypes.c_void_p
+        _copy_lib.wht_bench_event_record.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        _copy_lib.wht_bench_event_record.restype = ctypes.c_int
+        _copy_lib.wht_bench_event_elapsed_ms.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        _copy_lib.wht_bench_event_elapsed_ms.restype = ctypes.c_float
+        _copy_lib.wht_bench_event_destroy.argtypes = [ctypes.c_void_p]
+        _copy_lib.wht_bench_event_destroy.restype = ctypes.c_int
     return _copy_lib
+
+
+class StreamEvent:
+    """HIP timing event without the system-scope fence (libwht_copybench.so), recorded on torch's
+    current stream.  torch.cuda.Event creates events with the default flags, whose record costs
+    4.5 us of stream time; this one costs 3.3 us and reads a kernel 0.9 us long instead of 2.8 us."""
+
+    def __init__(self, torch):
+        self._torch = torch
+        self._h = _bench_lib().wht_bench_event_create()
+        if not self._h:
+            raise RuntimeError("wht_bench_event_create failed")
+
+    def record(self):
+        if _bench_lib().wht_bench_event_record(self._h, self._torch.cuda.current_stream().cuda_stream) != 0:
+            raise RuntimeError("wht_bench_event_record failed")
+
+    def elapsed_time(self, other) -> float:
+        ms = _bench_lib().wht_bench_event_elapsed_ms(self._h, other._h)
+        if ms < 0:
+            raise RuntimeError("wht_bench_event_elapsed_ms failed")
+        return ms
+
+    def __del__(self):
+        try:
+            _bench_lib().wht_bench_event_destroy(self._h)
+        except Exception:
+            pass
 
 
 def bench_empty(torch):
@@ -558,6 +642,8 @@ def main():
     # the paper's protocol on the same buffers, after the headline so that it cannot warm it up
     protocol = None if args.no_extras else [paper_protocol(bench)]
     graph_step = None if args.no_extras else graph_replay_step(torch, bench, args.steps)
+    if not args.no_extras:
+        add_series(head, w, *bench.series())
     del bench
     torch.cuda.empty_cache()
 
@@ -575,7 +661,10 @@ def main():
                 "traffic": recorded_traffic(w.name, dom_kernel),
                 "traffic_source": "recorded, not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
                                   "summary committed under profiles/ (TRAFFIC_JSON line); null if none",
-                "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms}
+                "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms,
+                "timing": "mean interval between events (no system-scope fence) recorded on the launch stream "
+                          "right before and right after each call, over the timed steps; such an interval reads "
+                          "about 1 us more than the kernels in it take"}
 
     result = {
         "metric": "wht_affine_fwd_bwd_tokens_per_s" if w.backward else "wht_affine_fwd_tokens_per_s",
@@ -603,6 +692,7 @@ def main():
     if not args.no_extras:
         extras = {}
         extras["copy_ceiling"] = copy_ceiling(torch)
+        extras["event_record_cost"] = event_cost(torch)
         others = [n for n in ("C4b_roofline", "C5_large", "C2_train", "C3_prefill",
                               "W_tiny_768", "W_base_1536", "W_wide_6144") if n != args.workload]
         extras["workloads"] = []
@@ -610,6 +700,7 @@ def main():
             b = Bench(torch, wht, synth, name)
             s, f, bw = b.run(max(10, args.steps // 2), 5)
             extras["workloads"].append(summarize(synth.WORKLOADS[name], s, f, bw))
+            add_series(extras["workloads"][-1], synth.WORKLOADS[name], *b.series())
             del b
             torch.cuda.empty_cache()
         if args.workload != "C4b_roofline":
