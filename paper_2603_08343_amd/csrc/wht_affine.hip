@@ -42,22 +42,29 @@ static int forward_cluster(int64_t N, int grid, bool resid) {
 // Few tokens (decoding): one token group per workgroup and no token loop.  Measured under HIP-graph
 // replay, bfloat16: 2.1 against 3.2 us per call for one token of 4096 elements, ahead of the
 // persistent kernel up to about 2^22 elements per call (2^21 for rows of 12 * 2^m elements) and level
-// with it there; both kernels do the same arithmetic in the same order, so the switch is invisible
-// in the results.
+// with it there; both kernels do the same arithmetic on a token in the same order, so the switch is
+// invisible in y (the norm statistic is summed in the order of the launch shape: its last bits may
+// differ between the two).
 template <class C>
 static bool few_tokens(int64_t N) { return N * C::kRow <= (C::kTwelve ? (1 << 21) : (1 << 22)); }
 
 template <class C>
 static int launch_forward_once(const void* x, const float* alpha, const float* beta, const void* resid,
-                               void* y, int64_t N, hipStream_t stream) {
+                               void* y, float* sumsq, int64_t N, hipStream_t stream) {
     using T = typename C::io::elem_t;
     const int grid = (int)((N + C::G - 1) / C::G);
-    if (resid)
+    if (resid && sumsq)
+        hipLaunchKernelGGL((forward_once_kernel<C, true, true>), dim3(grid), dim3(C::BT), 0, stream,
+                           static_cast<const T*>(x), alpha, beta, static_cast<const T*>(resid), static_cast<T*>(y),
+                           sumsq, N);
+    else if (resid)
         hipLaunchKernelGGL((forward_once_kernel<C, true>), dim3(grid), dim3(C::BT), 0, stream,
-                           static_cast<const T*>(x), alpha, beta, static_cast<const T*>(resid), static_cast<T*>(y), N);
+                           static_cast<const T*>(x), alpha, beta, static_cast<const T*>(resid), static_cast<T*>(y),
+                           static_cast<float*>(nullptr), N);
     else
         hipLaunchKernelGGL((forward_once_kernel<C, false>), dim3(grid), dim3(C::BT), 0, stream,
-                           static_cast<const T*>(x), alpha, beta, static_cast<const T*>(nullptr), static_cast<T*>(y), N);
+                           static_cast<const T*>(x), alpha, beta, static_cast<const T*>(nullptr), static_cast<T*>(y),
+                           static_cast<float*>(nullptr), N);
     return hipGetLastError() == hipSuccess ? WHT_OK : WHT_ERR_LAUNCH;
 }
 
@@ -135,8 +142,8 @@ template <class CF, class CB = CF, class CO = CF>
 static int run(Op op, Args& a) {
     switch (op) {
     case Op::Forward:
-        if (!a.sumsq && few_tokens<CO>(a.N))
-            return launch_forward_once<CO>(a.x, a.alpha, a.beta, a.resid, a.y, a.N, a.stream);
+        if (few_tokens<CO>(a.N))
+            return launch_forward_once<CO>(a.x, a.alpha, a.beta, a.resid, a.y, a.sumsq, a.N, a.stream);
         return launch_forward<CF>(a.x, a.alpha, a.beta, a.resid, a.y, a.sumsq, a.N, a.stream);
     case Op::Backward: return launch_backward<CB>(a.dy, a.x, a.alpha, a.dx, a.dalpha, a.dbeta, a.N,
                                                   a.workspace, a.stream);

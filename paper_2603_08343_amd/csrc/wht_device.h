@@ -657,6 +657,35 @@ struct Walker {
     }
 };
 
+// sumsq[tok] = sum of the token's r[i]^2 (the values as they stand, before rounding for the store):
+// each thread squares its values, the lanes of a token add up by butterfly shuffles, and a token that
+// spans several waves adds the wave sums through `wave_sums` (one float per wave of the workgroup)
+// in a fixed order, behind one workgroup barrier that every wave passes.
+template <class C>
+__device__ __forceinline__ void token_sumsq(const float (&r)[C::E], float* wave_sums, float* __restrict__ sumsq,
+                                            int64_t tok, int64_t N, unsigned t, unsigned slot, bool lane_ok) {
+    float sq = 0.0f;
+#pragma unroll
+    for (int i = 0; i < C::E; ++i) sq = fmaf(r[i], r[i], sq);
+    if (C::kTwelve && !lane_ok) sq = 0.0f;                  // padding lanes hold no elements
+    constexpr int kLanes = C::TPT < 64 ? C::TPT : 64;       // lanes of one wave that share a token
+#pragma unroll
+    for (int off = 1; off < kLanes; off <<= 1) sq += __shfl_xor(sq, off);
+    if constexpr (C::TPT <= 64) {
+        if (t == 0 && tok < N) sumsq[tok] = sq;
+    } else {
+        constexpr int kWaves = C::TPT / 64;                 // waves per token
+        if ((threadIdx.x & 63u) == 0) wave_sums[threadIdx.x >> 6] = sq;
+        exchange_barrier();
+        if (t == 0 && tok < N) {
+            float total = 0.0f;
+#pragma unroll
+            for (int wv = 0; wv < kWaves; ++wv) total += wave_sums[slot * kWaves + wv];
+            sumsq[tok] = total;
+        }
+    }
+}
+
 // forward:  y = (alpha / sqrt d) (.) (H_raw x) + beta      [+ resid when RESID]
 //
 // Per iteration k (x(k) [and resid(k)] have landed in their stages):
@@ -745,28 +774,7 @@ __global__ __launch_bounds__(C::BT) void forward_kernel(const typename C::io::el
             for (int i = 0; i < C::E; ++i) r[i] = fmaf(r[i], a[i], b[i]);
         }
         const int64_t tok = wk.token(grp);
-        if constexpr (STATS) {
-            float sq = 0.0f;
-#pragma unroll
-            for (int i = 0; i < C::E; ++i) sq = fmaf(r[i], r[i], sq);
-            if (C::kTwelve && !tm.last_ok) sq = 0.0f;          // padding lanes hold no elements
-            constexpr int kLanes = C::TPT < 64 ? C::TPT : 64;   // lanes of one wave that share a token
-#pragma unroll
-            for (int off = 1; off < kLanes; off <<= 1) sq += __shfl_xor(sq, off);
-            if constexpr (C::TPT <= 64) {
-                if (t == 0 && tok < N) sumsq[tok] = sq;
-            } else {
-                constexpr int kWaves = C::TPT / 64;             // waves per token
-                if ((threadIdx.x & 63u) == 0) wave_sums[threadIdx.x >> 6] = sq;
-                exchange_barrier();
-                if (t == 0 && tok < N) {
-                    float total = 0.0f;
-#pragma unroll
-                    for (int wv = 0; wv < kWaves; ++wv) total += wave_sums[wk.slot * kWaves + wv];
-                    sumsq[tok] = total;
-                }
-            }
-        }
+        if constexpr (STATS) token_sumsq<C>(r, wave_sums, sumsq, tok, N, t, wk.slot, tm.last_ok);
         if (more) wait_vmem<0>();
         global_put<C, LAST, !C::kTwelve>(r, y + tok * C::kRow, tm.last_elem, tok < N && tm.last_ok);
     }
@@ -791,12 +799,15 @@ __device__ __forceinline__ void global_get(uint4 (&raw)[C::NV], const typename C
 // long, so everything the group needs -- x, alpha, beta, the residual -- is requested at once,
 // straight into registers, before anything is awaited; there is no token loop, no prefetch stage and
 // no walk over the grid, whose set-up costs the persistent kernel about a microsecond per launch.
-template <class C, bool RESID>
+template <class C, bool RESID, bool STATS = false>
 __global__ __launch_bounds__(C::BT) void forward_once_kernel(const typename C::io::elem_t* x,
                                                              const float* __restrict__ alpha,
                                                              const float* __restrict__ beta,
                                                              const typename C::io::elem_t* resid,
-                                                             typename C::io::elem_t* y, int64_t N) {
+                                                             typename C::io::elem_t* y,
+                                                             float* __restrict__ sumsq, int64_t N) {
+    static_assert(!STATS || RESID, "the statistic belongs to the residual-stream output");
+    __shared__ float wave_sums[STATS ? C::BT / 64 : 1];
     __shared__ __align__(16) float lds[C::kExchangeBytes / 4];
     constexpr int LAST = C::P - 1;
     const unsigned t = threadIdx.x % C::TPT, slot = threadIdx.x / C::TPT;
@@ -825,6 +836,7 @@ __global__ __launch_bounds__(C::BT) void forward_once_kernel(const typename C::i
 #pragma unroll
         for (int i = 0; i < C::E; ++i) r[i] = fmaf(r[i], a[i], b[i]);
     }
+    if constexpr (STATS) token_sumsq<C>(r, wave_sums, sumsq, tok, N, t, slot, tm.last_ok);
     global_put<C, LAST, false>(r, y + tok * C::kRow, tm.last_elem, tok < N && tm.last_ok);
 }
 

@@ -231,11 +231,17 @@ def test_forward_few_tokens(d, dtype, N):
     buf, bufr = nan_filled(N + 1, d, dtype), nan_filled(N + 1, d, dtype)
     y = wht.wht_affine_forward(x, a, b, y=buf[:N])
     yr = wht.wht_affine_forward_residual(x, a, b, resid, y=bufr[:N])
+    ys, sumsq = wht.wht_affine_forward_residual_stats(x, a, b, resid)
     torch.cuda.synchronize()
     assert_io_close(y, oracle.forward(inp.x, inp.alpha, inp.beta, _method(d)), dtype, f"few d={d} N={N} y")
     assert_io_close(yr, oracle.forward_residual(inp.x, inp.alpha, inp.beta, inp.dy, _method(d)), dtype,
                     f"few d={d} N={N} y+resid")
     assert bool(torch.isnan(buf[N].float()).all()) and bool(torch.isnan(bufr[N].float()).all())
+    # with the norm statistic: the same y, and the statistic of the unrounded values
+    bits = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(ys.view(bits), yr.view(bits))
+    _, ref_sq = oracle.forward_residual_stats(inp.x, inp.alpha, inp.beta, inp.dy, _method(d))
+    np.testing.assert_allclose(to_f64(sumsq), ref_sq, rtol=1e-5)
 
 
 @pytest.mark.parametrize("d,dtype", [(d, "bf16") for d in ALL_D + TWELVE_D] + [(d, "f32") for d in ALL_D[:-1]])
@@ -255,6 +261,25 @@ def test_forward_on_both_sides_of_the_few_token_limit(d, dtype):
     assert torch.equal(y_few.view(bits), y_all[:lim].view(bits))
     _assert_all_tokens(y_all, lambda lo, hi: oracle.forward(inp.x[lo:hi], inp.alpha, inp.beta, "fast"),
                        N, dtype, f"limit d={d} y")
+
+
+@pytest.mark.parametrize("d,dtype", [(256, "f32"), (512, "bf16"), (1024, "bf16"), (2048, "bf16"), (4096, "bf16"),
+                                     (768, "bf16"), (6144, "bf16"), (16384, "bf16"), (4096, "f32")])
+def test_forward_residual_stats_above_the_few_token_limit(d, dtype):
+    # the persistent kernel's residual + statistic variant, ragged last group, every width class
+    N = _few_token_limit(d) + 37
+    _announce(f"forward+residual+stats above the few-token limit d={d} {dtype} N={N}")
+    inp = synth.make_inputs(N, d, dtype, seed=d + 13)
+    x, resid = to_gpu(inp.x, dtype), to_gpu(inp.dy, dtype)
+    a, b = torch.from_numpy(inp.alpha).cuda(), torch.from_numpy(inp.beta).cuda()
+    y, ss = wht.wht_affine_forward_residual_stats(x, a, b, resid, y=nan_filled(N, d, dtype))
+    torch.cuda.synchronize()
+    got = to_f64(ss)
+    for lo in range(0, N, CHUNK):
+        hi = min(N, lo + CHUNK)
+        ref_y, ref_ss = oracle.forward_residual_stats(inp.x[lo:hi], inp.alpha, inp.beta, inp.dy[lo:hi], "fast")
+        assert_io_close(y[lo:hi], ref_y, dtype, f"stats above limit d={d} y tokens {lo}..{hi - 1}")
+        assert np.max(np.abs(got[lo:hi] - ref_ss) / ref_ss) <= 1e-5
 
 
 # ------------------------------------------------------------------ residual add fused into the epilogue
