@@ -673,7 +673,7 @@ def main():
         "vs_baseline": None,
         # what the path computes in: float32 vector arithmetic and float32 accumulation; on the
         # matrix-core schedule (bf16 I/O, d >= 1024) a float32 value enters a +-1 matrix round as two
-        # bfloat16 terms hi + lo (relative error <= 2^-18), the round's products being exact
+        # bfloat16 terms hi + lo (relative error <= 2^-17), the round's products being exact
         "dtype": "f32 (matrix-core rounds on bf16 hi+lo pairs, f32 accumulate)" if w.dtype == "bf16" and w.d >= 768
                  else "f32",
         "data": "synthetic",

@@ -40,7 +40,7 @@
  *     For bfloat16 tensors of d >= 1024 (and all 12 * 2^m widths) ten of the log2(d) stages run on
  *     the matrix cores as products with +-1 matrices: exact products, float32 accumulation, and a
  *     float32 value entering such a product is represented as the sum of two bfloat16 terms, which
- *     carries it to a relative error of at most 2^-18 (three orders of magnitude below the bfloat16
+ *     carries it to a relative error of at most 2^-17 (five hundred times finer than the bfloat16
  *     output's own rounding).  float32 tensors never take this path.
  *   - Non-finite inputs: NaN propagates.  An infinite input makes the token's outputs +-Inf or NaN
  *     with float32 tensors (Inf - Inf in a butterfly) and NaN with bfloat16 tensors of d >= 1024

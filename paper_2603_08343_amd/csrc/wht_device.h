@@ -541,7 +541,7 @@ __device__ __forceinline__ f32x16 hadamard_round_bf16(const uint4& a_lo, const u
 }
 
 // One round on float32 data: each value is split into bf16 hi + bf16 lo (hi = RNE(v), lo =
-// RNE(v - hi); v - hi is exact, so |v - hi - lo| <= 2^-18 |v|) and both parts go through the same
+// RNE(v - hi); v - hi is exact, so |v - hi - lo| <= 2^-17 |v|) and both parts go through the same
 // +-1 product, accumulated in float32.  v - hi is formed with plain vector instructions (widen hi by
 // a shift / a mask, subtract): the bf16 dot-product instruction would do it in one, but it executes
 // on the matrix pipeline and stalls behind the rounds' own MFMAs (measured: 20 cycles per dot
