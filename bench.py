@@ -417,6 +417,7 @@ def decode_latency(torch, wht, synth, iters=1000):
         dense = dense_wo(torch, w, iters=200)
         row = {"N": w.N, "d": w.d, "wht_affine_us_per_call": us, "dense_wo_us_per_call": dense["fwd_ms"] * 1e3,
                "wht_affine_us_per_call_graph": None, "dense_wo_us_per_call_graph": None,
+               "wht_affine_residual_stats_us_per_call_graph": None,
                "empty_kernel_us_per_call_graph": None, "copy_same_bytes_us_per_call_graph": None}
         try:
             per_graph = 50
@@ -424,7 +425,13 @@ def decode_latency(torch, wht, synth, iters=1000):
             Wd = torch.randn(w.d, w.d, device="cuda", dtype=torch.bfloat16) / (w.d ** 0.5)
             bd = torch.zeros(w.d, device="cuda", dtype=torch.bfloat16)
             yd = torch.empty_like(xd)
+            rd = torch.randn(w.N, w.d, device="cuda", dtype=torch.bfloat16)
+            ss = torch.empty(w.N, device="cuda", dtype=torch.float32)
             for key, fn in (("wht_affine_us_per_call_graph", lambda: b.fwd(0)),
+                            # the layer as the attention block calls it when decoding: residual add fused,
+                            # in place on the residual stream, with the following RMS norm's statistic
+                            ("wht_affine_residual_stats_us_per_call_graph",
+                             lambda: wht.wht_affine_forward_residual_stats(b.x[0], b.alpha, b.beta, rd, y=rd, sumsq=ss)),
                             ("dense_wo_us_per_call_graph", lambda: torch.addmm(bd, xd, Wd.t())),
                             # floors of a call on this GPU: a kernel that does nothing, and a plain copy
                             # of the same x -> y bytes (one memory round trip, no arithmetic)
