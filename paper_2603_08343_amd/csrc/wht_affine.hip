@@ -39,14 +39,18 @@ static int forward_cluster(int64_t N, int grid, bool resid) {
     return grid;
 }
 
-// Few tokens (decoding): one token group per workgroup and no token loop.  Measured under HIP-graph
-// replay, bfloat16: 2.1 against 3.2 us per call for one token of 4096 elements, ahead of the
-// persistent kernel up to about 2^22 elements per call (2^21 for rows of 12 * 2^m elements) and level
-// with it there; both kernels do the same arithmetic on a token in the same order, so the switch is
-// invisible in y (the norm statistic is summed in the order of the launch shape: its last bits may
-// differ between the two).
+// Few tokens (decoding, short prefills): one token group per workgroup and no token loop.  Measured
+// under HIP-graph replay, bfloat16: 2.1 against 3.2 us per call for one token of 4096 elements.  The
+// persistent kernel takes over where the two break even: 2^22 elements per call at d >= 4096 (and for
+// the butterfly schedule), 2^24 for the matrix-core schedule at d = 1024 and 2048 (16384 tokens of
+// 1024 elements: 12.0 against 13.3 us), 2^21 for rows of 12 * 2^m elements.  Both kernels do the same
+// arithmetic on a token in the same order, so the switch is invisible in y (the norm statistic is
+// summed in the order of the launch shape: its last bits may differ between the two).
 template <class C>
-static bool few_tokens(int64_t N) { return N * C::kRow <= (C::kTwelve ? (1 << 21) : (1 << 22)); }
+static bool few_tokens(int64_t N) {
+    const int64_t limit = C::kTwelve ? (1 << 21) : ((C::kMfma && C::n <= 11) ? (1 << 24) : (1 << 22));
+    return N * C::kRow <= limit;
+}
 
 template <class C>
 static int launch_forward_once(const void* x, const float* alpha, const float* beta, const void* resid,

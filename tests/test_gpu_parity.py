@@ -206,16 +206,21 @@ def test_many_passes_per_workgroup():
 
 # ------------------------------------------------------------------ few tokens per call (decoding)
 #
-# Calls of up to FEW_TOKEN_ELEMS elements (half that for d = 12 * 2^m) run on a kernel of their own:
+# Calls of up to 2^22 elements (2^24 for bfloat16 rows of 1024 and 2048 elements, 2^21 for d = 12 * 2^m)
+# run on a kernel of their own:
 # one token group per workgroup, no token loop.  The small cases above pass through it; the cases
 # here pin the decode shapes of the paper's Table 2 widths, the hand-over to the persistent kernel
 # and that kernel just above the limit, where it has the fewest passes per workgroup.
 
-FEW_TOKEN_ELEMS = 1 << 22
-
-
-def _few_token_limit(d):
-    return (FEW_TOKEN_ELEMS // 2 if d % 3 == 0 else FEW_TOKEN_ELEMS) // d
+def _few_token_limit(d, dtype="bf16"):
+    """Largest N that runs the one-pass kernel (the library's rule, restated)."""
+    if d % 3 == 0:
+        elems = 1 << 21
+    elif dtype == "bf16" and d in (1024, 2048):
+        elems = 1 << 24
+    else:
+        elems = 1 << 22
+    return elems // d
 
 
 @pytest.mark.parametrize("N", [1, 16, 64, 256])
@@ -248,7 +253,7 @@ def test_forward_few_tokens(d, dtype, N):
 def test_forward_on_both_sides_of_the_few_token_limit(d, dtype):
     # N = limit runs the one-pass kernel, N = limit + 37 the persistent one (ragged last group): both
     # against the oracle, and bit for bit against each other on the rows they share.
-    lim = _few_token_limit(d)
+    lim = _few_token_limit(d, dtype)
     N = lim + 37
     _announce(f"few-token limit d={d} {dtype}: N={lim} and N={N}")
     inp = synth.make_inputs(N, d, dtype, seed=d + 11, backward=False)
@@ -267,7 +272,7 @@ def test_forward_on_both_sides_of_the_few_token_limit(d, dtype):
                                      (768, "bf16"), (6144, "bf16"), (16384, "bf16"), (4096, "f32")])
 def test_forward_residual_stats_above_the_few_token_limit(d, dtype):
     # the persistent kernel's residual + statistic variant, ragged last group, every width class
-    N = _few_token_limit(d) + 37
+    N = _few_token_limit(d, dtype) + 37
     _announce(f"forward+residual+stats above the few-token limit d={d} {dtype} N={N}")
     inp = synth.make_inputs(N, d, dtype, seed=d + 13)
     x, resid = to_gpu(inp.x, dtype), to_gpu(inp.dy, dtype)
