@@ -108,11 +108,19 @@ def wht_affine_version() -> int:
 
 # ------------------------------------------------------------------ tensor calls
 
+_torch_module = None
+
+
 def _torch():
-    import torch
-    if not torch.cuda.is_available():
-        raise RuntimeError("wht_affine needs an AMD GPU (gfx950); there is no CPU fallback")
-    return torch
+    """torch, once a GPU has been seen (checked on the first call only: a decoding loop calls this
+    binding every few microseconds)."""
+    global _torch_module
+    if _torch_module is None:
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("wht_affine needs an AMD GPU (gfx950); there is no CPU fallback")
+        _torch_module = torch
+    return _torch_module
 
 
 def _dtype_code(t, torch):
@@ -137,8 +145,30 @@ def _check_param(p, name, d, x, torch):
 
 
 def _stream_handle(stream, torch, device):
-    s = stream if stream is not None else torch.cuda.current_stream(device)
-    return s.cuda_stream
+    if stream is not None:
+        return stream.cuda_stream
+    raw = getattr(torch._C, "_cuda_getCurrentRawStream", None)     # the handle without a Stream object
+    if raw is not None and device.index is not None:
+        return raw(device.index)
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+class _DeviceGuard:
+    """`with torch.cuda.device(dev)` only when dev is not the current device already."""
+
+    def __init__(self, torch, device):
+        self._ctx = None
+        if device.index is not None and device.index != torch.cuda.current_device():
+            self._ctx = torch.cuda.device(device)
+
+    def __enter__(self):
+        if self._ctx is not None:
+            self._ctx.__enter__()
+
+    def __exit__(self, *exc):
+        if self._ctx is not None:
+            return self._ctx.__exit__(*exc)
+        return False
 
 
 def wht_affine_forward(x, alpha, beta, y=None, stream=None):
@@ -154,7 +184,7 @@ def wht_affine_forward(x, alpha, beta, y=None, stream=None):
         _check_io(y, "y", torch, like=x)
     # torch gives an empty tensor a NULL address; the library never touches x, y when N = 0
     xp, yp = (x.data_ptr(), y.data_ptr()) if N > 0 else (alpha.data_ptr(), alpha.data_ptr())
-    with torch.cuda.device(x.device):
+    with _DeviceGuard(torch, x.device):
         rc = wht_affine_forward_raw(xp, alpha.data_ptr(), beta.data_ptr(), yp, N, d,
                                     _dtype_code(x, torch), _stream_handle(stream, torch, x.device))
     if rc != 0:
@@ -175,7 +205,7 @@ def wht_affine_forward_residual(x, alpha, beta, resid, y=None, stream=None):
     else:
         _check_io(y, "y", torch, like=x)
     ptrs = (x.data_ptr(), resid.data_ptr(), y.data_ptr()) if N > 0 else (alpha.data_ptr(),) * 3
-    with torch.cuda.device(x.device):
+    with _DeviceGuard(torch, x.device):
         rc = wht_affine_forward_residual_raw(ptrs[0], alpha.data_ptr(), beta.data_ptr(), ptrs[1], ptrs[2], N, d,
                                              _dtype_code(x, torch), _stream_handle(stream, torch, x.device))
     if rc != 0:
@@ -202,7 +232,7 @@ def wht_affine_forward_residual_stats(x, alpha, beta, resid, y=None, sumsq=None,
             or sumsq.device != x.device:
         raise ValueError("sumsq must be a contiguous float32 [N] tensor on x's device")
     ptrs = (x.data_ptr(), resid.data_ptr(), y.data_ptr(), sumsq.data_ptr()) if N > 0 else (alpha.data_ptr(),) * 4
-    with torch.cuda.device(x.device):
+    with _DeviceGuard(torch, x.device):
         rc = wht_affine_forward_residual_stats_raw(ptrs[0], alpha.data_ptr(), beta.data_ptr(), ptrs[1], ptrs[2],
                                                    ptrs[3], N, d, _dtype_code(x, torch),
                                                    _stream_handle(stream, torch, x.device))
@@ -257,7 +287,7 @@ def wht_affine_backward(dy, x, alpha, dx=None, dalpha=None, dbeta=None, workspac
     dy_p = dy.data_ptr() if N > 0 else dummy
     x_p = 0 if not want_param_grads else (x.data_ptr() if N > 0 else dummy)
     dx_p = 0 if dx is None else (dx.data_ptr() if N > 0 else dummy)
-    with torch.cuda.device(dy.device):
+    with _DeviceGuard(torch, dy.device):
         rc = wht_affine_backward_raw(dy_p, x_p, alpha.data_ptr(), dx_p,
                                      dalpha.data_ptr() if dalpha is not None else 0,
                                      dbeta.data_ptr() if dbeta is not None else 0, N, d, code,
@@ -291,7 +321,7 @@ def wht_affine_backward_static(dy, x, alpha, dx=None, dalpha=None, dbeta=None, s
         _check_param(dbeta, "dbeta", d, dy, torch)
     dummy = alpha.data_ptr()
     ptrs = (dy.data_ptr(), x.data_ptr(), dx.data_ptr()) if N > 0 else (dummy,) * 3
-    with torch.cuda.device(dy.device):
+    with _DeviceGuard(torch, dy.device):
         rc = wht_affine_backward_static_raw(ptrs[0], ptrs[1], alpha.data_ptr(), ptrs[2], dalpha.data_ptr(),
                                             dbeta.data_ptr(), N, d, _dtype_code(dy, torch),
                                             _stream_handle(stream, torch, dy.device))
