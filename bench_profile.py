@@ -18,6 +18,8 @@ Three sub-commands:
              events and followed by a probe of the shader clock: shows the clock transient that a
              short benchmark run sits in
                  python3 bench_profile.py series --workload C5_large --steps 80
+             with --copy the steps are plain copies of 512 MiB (the bench-only copy kernel) instead:
+             the transient without the layer's arithmetic
 
 Nothing here is on the product path (the file sits beside bench.py, outside the package).
 """
@@ -74,9 +76,29 @@ def series(args):
     import paper_2603_08343_amd as wht
     from paper_2603_08343_amd import synth
 
+    K = args.steps
+    if args.copy:
+        n = 512 << 20
+        src = [torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255) for _ in range(3)]
+        dst = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(3)]
+        probes = torch.zeros(K, 2, dtype=torch.int64, device="cuda")
+        ev = [[bench.StreamEvent(torch) for _ in range(2)] for _ in range(K)]
+        torch.cuda.synchronize()
+        time.sleep(args.idle)
+        for i in range(K):
+            ev[i][0].record()
+            bench.bench_copy(torch, src[i % 3], dst[i % 3])
+            ev[i][1].record()
+            bench.bench_clock_probe(torch, probes[i])
+        torch.cuda.synchronize()
+        p = probes.cpu().numpy()
+        print(f"plain copy of 512 MiB (copy_kernel, bench-only library); {K} steps after {args.idle} s of idling")
+        print("step copy_us shader_MHz")
+        for i in range(K):
+            print(f"{i:4d} {ev[i][0].elapsed_time(ev[i][1]) * 1e3:7.1f} {100.0 * p[i][0] / max(1, p[i][1]):8.0f}")
+        return
     w = synth.WORKLOADS[args.workload]
     b = bench.Bench(torch, wht, synth, args.workload)
-    K = args.steps
     probes = torch.zeros(K, 2, dtype=torch.int64, device="cuda")
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
     torch.cuda.synchronize()
@@ -223,6 +245,7 @@ def main():
     c.add_argument("--workload", default="C5_large")
     c.add_argument("--steps", type=int, default=80)
     c.add_argument("--idle", type=float, default=1.0, help="seconds of idling before the first step")
+    c.add_argument("--copy", action="store_true", help="time plain 512 MiB copies instead of the layer")
     c.set_defaults(fn=series)
     s = sub.add_parser("summarize")
     s.add_argument("--workload", default="C5_large")
