@@ -695,3 +695,26 @@ def test_bench_copy_kernel_copies():
     bench.bench_copy(torch, src, dst)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
+
+
+def test_bench_stream_events_time_a_known_interval():
+    # the benchmark's events (bench-only library, no system-scope fence) against torch's on the same
+    # stream, around the same 64 MiB copy: the two clocks must agree to a few microseconds
+    import bench
+    src = torch.randint(-2 ** 31, 2 ** 31 - 1, (16 << 20,), dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    for _ in range(3):
+        bench.bench_copy(torch, src, dst)
+    a, b = bench.StreamEvent(torch), bench.StreamEvent(torch)
+    ta, tb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    ta.record()
+    a.record()
+    for _ in range(10):
+        bench.bench_copy(torch, src, dst)
+    b.record()
+    tb.record()
+    torch.cuda.synchronize()
+    ours, theirs = a.elapsed_time(b), ta.elapsed_time(tb)
+    assert 0.0 < ours <= theirs + 0.002
+    assert theirs - ours < 0.05
